@@ -1,0 +1,243 @@
+"""CPU oracle for the expert-choice MoE layer (TEST INFRASTRUCTURE ONLY).
+
+A plain, slow, float64 numpy statement of what the layer computes, written
+from the paper's definitions: capacity (Sec. 3.2, Eq. 1), gating and TopK over
+the token axis (Eq. 2), gather and expert FFN (Eq. 3), gate-weighted combine
+(Eq. 4).  The backward pass is not printed in the paper; it is the derivative
+of Eq. 2-4 with the TopK indices held constant (Sec. 3.4 says the gate is
+trained, so gradient reaches W_g through the selected gate values G).
+
+Only tests, the smoke check and the bench's cpu_baseline leg may import this
+module.  It shares no code with the HIP path and must never be used by it.
+
+Conventions (paper notation):
+  X[n,d]  tokens;  Wg[d,e] expert embeddings;  S[n,e] affinity scores;
+  I[e,k] int32 token index of the j-th selected token of expert i;
+  G[e,k] gate weight S[I[i,j], i];  X_in[e,k,d];  W1[e,d,d_ff];  W2[e,d_ff,d]
+  (the paper keeps W2[i] as [d,d_ff] and multiplies by its transpose; storing
+  [d_ff,d] and multiplying untransposed is the same mathematics);
+  X_e[e,k,d];  X_out[n,d].
+
+Readings where the paper is silent (each listed in the design notes too):
+  * TopK ties go to the lower token index; a bucket is ordered by descending
+    score, ties by ascending token index.
+  * k = floor(n*c/e) evaluated in double.
+  * Softmax is over the expert axis (one distribution per token).
+  * G is the raw score (no renormalisation per token).
+  * GeLU is the exact erf form; no biases; tokens chosen by nobody get 0.
+  * S is stored in float32 (the interface type); TopK acts on those float32
+    values, so ties are decided on float32 bit patterns.
+
+bfloat16 tensors arrive as uint16 bit patterns and are widened exactly.
+
+parity pins: every function here is pinned by tests/test_oracle_pins.py
+(brute-force selection, dense one-hot einsum of Eq. 3/4, closed forms for
+degenerate routings, textbook dense FFN for e=1, finite differences and an
+autograd restatement for the backward).
+"""
+from __future__ import annotations
+
+import math
+from typing import Dict, Optional, Tuple
+
+import numpy as np
+from scipy.special import erf as _erf
+
+ACT_RELU = 0
+ACT_GELU = 1
+ACT_IDENTITY = 2
+
+
+def widen(a: np.ndarray) -> np.ndarray:
+    """float64 copy of a tensor stored as float32/float64 or as bf16 bits."""
+    a = np.asarray(a)
+    if a.dtype == np.uint16:  # bfloat16 bit pattern: upper half of a float32
+        return (a.astype(np.uint32) << np.uint32(16)).view(np.float32).astype(np.float64)
+    return a.astype(np.float64)
+
+
+# ------------------------------------------------------------------ Eq. 1 ---
+def capacity(n: int, c: float, e: int) -> int:
+    """Bucket size k = n*c/e (Sec. 3.2, Eq. 1), floored when not integral."""
+    if n <= 0 or e <= 0 or not (c > 0):
+        raise ValueError("n, e and c must be positive")
+    k = int(math.floor(float(n) * float(c) / float(e)))
+    if k < 1 or k > n:
+        raise ValueError(f"capacity k={k} outside [1, n={n}]")
+    return k
+
+
+# ------------------------------------------------------------------ Eq. 2 ---
+def gate(X: np.ndarray, Wg: np.ndarray, out_dtype=np.float32) -> np.ndarray:
+    """S = Softmax(X . Wg) over the expert axis (Sec. 3.2, Eq. 2; Sec. 3.4).
+
+    Returns S[n,e] rounded to float32, the type the interface carries
+    (out_dtype=np.float64 keeps the unrounded scores, for derivative checks).
+    """
+    Z = widen(X) @ widen(Wg)                       # [n,e] token-to-expert logits
+    Z = Z - Z.max(axis=1, keepdims=True)           # shift invariance of softmax
+    P = np.exp(Z)
+    S = P / P.sum(axis=1, keepdims=True)
+    return S.astype(out_dtype)
+
+
+def topk_tokens(S: np.ndarray, k: int) -> Tuple[np.ndarray, np.ndarray]:
+    """G, I = TopK(S^T, k): every expert takes its k best tokens (Eq. 2).
+
+    S is float32 [n,e].  For expert i the tokens are ranked by descending
+    S[:, i]; equal scores rank by ascending token index (stable sort), which
+    settles both who is admitted at the k-th place and the bucket order.
+    """
+    S = np.asarray(S)
+    if S.dtype != np.float32:
+        raise TypeError("TopK acts on the float32 scores")
+    n, e = S.shape
+    if not (1 <= k <= n):
+        raise ValueError("k outside [1, n]")
+    I = np.empty((e, k), dtype=np.int32)
+    G = np.empty((e, k), dtype=np.float32)
+    for i in range(e):
+        col = S[:, i]
+        order = np.argsort(-col, kind="stable")    # descending score, ties: low index first
+        I[i, :] = order[:k]
+        G[i, :] = col[order[:k]]
+    return G, I
+
+
+# ------------------------------------------------------------------ Eq. 3 ---
+def dispatch(X: np.ndarray, I: np.ndarray) -> np.ndarray:
+    """X_in = P . X with P = Onehot(I): X_in[i,j,:] = X[I[i,j],:] (Eq. 3).
+
+    A pure gather; the storage type of X is kept (so it can be compared
+    bit for bit).
+    """
+    X = np.asarray(X)
+    return X[np.asarray(I, dtype=np.int64), :]
+
+
+def activation(A: np.ndarray, act: int) -> np.ndarray:
+    if act == ACT_RELU:
+        return np.maximum(A, 0.0)
+    if act == ACT_GELU:                              # a * Phi(a), exact erf form
+        return 0.5 * A * (1.0 + _erf(A / math.sqrt(2.0)))
+    if act == ACT_IDENTITY:
+        return A
+    raise ValueError("unknown activation")
+
+
+def activation_grad(A: np.ndarray, act: int) -> np.ndarray:
+    if act == ACT_RELU:
+        return (A > 0.0).astype(np.float64)
+    if act == ACT_GELU:                              # Phi(a) + a * phi(a)
+        Phi = 0.5 * (1.0 + _erf(A / math.sqrt(2.0)))
+        phi = np.exp(-0.5 * A * A) / math.sqrt(2.0 * math.pi)
+        return Phi + A * phi
+    if act == ACT_IDENTITY:
+        return np.ones_like(A)
+    raise ValueError("unknown activation")
+
+
+def expert_ffn(X_in: np.ndarray, W1: np.ndarray, W2: np.ndarray, act: int,
+               return_hidden: bool = False):
+    """X_e[i] = act(X_in[i] . W1[i]) . W2[i], no bias (Eq. 3).
+
+    W2 is stored [e,d_ff,d] (the paper's W2[i]^T).  float64 throughout, no
+    intermediate rounding.
+    """
+    X_in = widen(X_in)
+    e, k, d = X_in.shape
+    d_ff = W1.shape[2]
+    X_e = np.empty((e, k, d), dtype=np.float64)
+    A_all = np.empty((e, k, d_ff), dtype=np.float64) if return_hidden else None
+    for i in range(e):
+        A = X_in[i] @ widen(W1[i])                  # [k,d_ff]
+        H = activation(A, act)
+        X_e[i] = H @ widen(W2[i])                   # [k,d]
+        if return_hidden:
+            A_all[i] = A
+    if return_hidden:
+        return X_e, A_all
+    return X_e
+
+
+# ------------------------------------------------------------------ Eq. 4 ---
+def combine(X_e: np.ndarray, G: np.ndarray, I: np.ndarray, n: int) -> np.ndarray:
+    """X_out[l,:] = sum_{i,j} P[i,j,l] G[i,j] X_e[i,j,:] (Eq. 4).
+
+    Tokens that no expert selected keep a zero row.
+    """
+    X_e = widen(X_e)
+    G = widen(G)
+    e, k, d = X_e.shape
+    X_out = np.zeros((n, d), dtype=np.float64)
+    for i in range(e):                              # experts ascending
+        for j in range(k):
+            X_out[I[i, j], :] += G[i, j] * X_e[i, j, :]
+    return X_out
+
+
+# ------------------------------------------------------------- whole layer ---
+def forward(X, Wg, W1, W2, c: float, act: int) -> Dict[str, np.ndarray]:
+    """Gate -> TopK over tokens -> gather -> expert FFN -> combine (Eq. 1-4).
+
+    W1 = W2 = None with act = ACT_IDENTITY gives identity experts (routing
+    only): X_e = X_in.
+    """
+    n, d = np.asarray(X).shape
+    e = np.asarray(Wg).shape[1]
+    k = capacity(n, c, e)
+    S = gate(X, Wg)
+    G, I = topk_tokens(S, k)
+    X_in = dispatch(X, I)
+    if W1 is None:
+        if act != ACT_IDENTITY:
+            raise ValueError("identity experts need act = ACT_IDENTITY")
+        X_e = widen(X_in)
+    else:
+        X_e = expert_ffn(X_in, W1, W2, act)
+    X_out = combine(X_e, G, I, n)
+    return {"k": k, "S": S, "G": G, "I": I, "X_in": X_in, "X_e": X_e, "X_out": X_out}
+
+
+# ---------------------------------------------------------------- backward ---
+def backward(X, Wg, W1, W2, act: int, S: np.ndarray, G: np.ndarray, I: np.ndarray,
+             dY: np.ndarray) -> Dict[str, np.ndarray]:
+    """Gradients of L = <dY, X_out> w.r.t. X, Wg, W1, W2 (derived from Eq. 2-4).
+
+    The selection I is a constant.  The gate values G[i,j] = S[I[i,j], i] are
+    differentiable, so W_g and X also receive gradient through the softmax.
+    S, G, I are the forward's routing tensors (float32 / int32), taken as
+    given so that the same selection is differentiated on both sides.
+    """
+    Xd, Wgd, dYd = widen(X), widen(Wg), widen(dY)
+    Sd, Gd = widen(S), widen(G)
+    n, d = Xd.shape
+    e, k = I.shape
+    Ii = np.asarray(I, dtype=np.int64)
+
+    X_in = Xd[Ii, :]                                            # [e,k,d]
+    dS = np.zeros((n, e), dtype=np.float64)
+    dX = np.zeros((n, d), dtype=np.float64)
+    dW1 = np.empty(np.asarray(W1).shape, dtype=np.float64)
+    dW2 = np.empty(np.asarray(W2).shape, dtype=np.float64)
+    for i in range(e):
+        W1i, W2i = widen(W1[i]), widen(W2[i])
+        A = X_in[i] @ W1i                                       # [k,d_ff]
+        H = activation(A, act)
+        X_e = H @ W2i                                           # [k,d]
+        dYsel = dYd[Ii[i], :]                                   # rows of dY this expert fed
+        dXe = Gd[i][:, None] * dYsel                            # dL/dX_e
+        dG = np.einsum("jt,jt->j", dYsel, X_e)                  # dL/dG[i,:]
+        dW2[i] = H.T @ dXe
+        dH = dXe @ W2i.T
+        dA = dH * activation_grad(A, act)
+        dW1[i] = X_in[i].T @ dA
+        dXin = dA @ W1i.T                                       # [k,d]
+        for j in range(k):                                      # each token at most once per expert
+            dX[Ii[i, j], :] += dXin[j, :]
+            dS[Ii[i, j], i] = dG[j]
+    # softmax backward, row by row: dZ = S * (dS - <dS, S>)
+    dZ = Sd * (dS - (dS * Sd).sum(axis=1, keepdims=True))
+    dWg = Xd.T @ dZ
+    dX += dZ @ Wgd.T
+    return {"dX": dX, "dWg": dWg, "dW1": dW1, "dW2": dW2, "dS": dS, "dZ": dZ}

@@ -1,0 +1,435 @@
+"""Pins for the CPU oracle: what the paper and the mathematics fix.
+
+Each test checks the oracle against something other than itself: hand-worked
+values (tests/golden), closed forms of degenerate routings, brute force in
+pure Python on tiny inputs, the dense one-hot einsum form of Eq. 3 / Eq. 4,
+textbook routines from an independent library (torch CPU float64), and
+finite differences for the derived backward.  No GPU is needed.
+"""
+import json
+import math
+import os
+
+import numpy as np
+import pytest
+import torch
+
+import workloads as wl
+from oracle import ec_moe_ref as ref
+
+
+def _rng(seed):
+    return np.random.default_rng(seed)
+
+
+@pytest.fixture(scope="module")
+def golden(golden_dir):
+    with open(os.path.join(golden_dir, "handworked_routing.json")) as f:
+        return json.load(f)
+
+
+# --------------------------------------------------------------- Eq. 1 ------
+def test_capacity_closed_form_and_sum_of_buckets():
+    # Eq. 1 on the five workloads: e*k == n*c exactly (c = average experts per token)
+    for w in wl.WORKLOADS.values():
+        k = ref.capacity(w.n, w.c, w.e)
+        assert k == w.k
+        assert k * w.e == int(w.n * w.c)
+    assert ref.capacity(256, 2.0, 8) == 64
+    assert ref.capacity(8192, 2.0, 16) == 1024
+    assert ref.capacity(65536, 1.0, 256) == 256
+    assert ref.capacity(10, 0.5, 3) == 1        # 1.67 floors to 1
+    assert ref.capacity(7, 7.0, 7) == 7         # c = e: every expert takes all tokens
+    with pytest.raises(ValueError):
+        ref.capacity(4, 0.5, 16)                # k < 1
+    with pytest.raises(ValueError):
+        ref.capacity(4, 8.0, 2)                 # k > n
+
+
+# --------------------------------------------------------------- Eq. 2 ------
+def test_gate_handworked(golden):
+    g = golden["gate_example"]
+    X = np.array(g["X"], dtype=np.float64)
+    Wg = np.log(np.array(g["Wg_log_of"], dtype=np.float64))
+    S = ref.gate(X, Wg, out_dtype=np.float64)
+    np.testing.assert_allclose(S, np.array(g["S"]), rtol=1e-14)
+
+
+def test_gate_rows_are_distributions_and_degenerate_cases():
+    r = _rng(1)
+    X = r.standard_normal((37, 19)).astype(np.float32)
+    Wg = (r.standard_normal((19, 5)) / math.sqrt(19)).astype(np.float32)
+    S = ref.gate(X, Wg)
+    assert S.dtype == np.float32 and S.shape == (37, 5)
+    assert (S >= 0).all()
+    np.testing.assert_allclose(S.astype(np.float64).sum(axis=1), 1.0, atol=1e-6)
+    # zero embeddings: uniform distribution, exactly 1/e
+    S0 = ref.gate(X, np.zeros_like(Wg))
+    assert (S0 == np.float32(1.0 / 5)).all()
+    # one expert: probability one
+    assert (ref.gate(X, Wg[:, :1]) == np.float32(1.0)).all()
+    # a constant added to every logit of a token changes nothing
+    Xa = np.concatenate([X, np.ones((37, 1), np.float32)], axis=1)
+    Wa = np.concatenate([Wg, np.full((1, 5), 3.25, np.float32)], axis=0)
+    np.testing.assert_allclose(ref.gate(Xa, Wa, np.float64), ref.gate(X, Wg, np.float64), rtol=1e-12)
+    # large logits do not overflow
+    Sbig = ref.gate(X * 1000.0, Wg, np.float64)
+    assert np.isfinite(Sbig).all()
+
+
+def test_gate_against_library_softmax():
+    r = _rng(2)
+    X = r.standard_normal((64, 48))
+    Wg = r.standard_normal((48, 7)) / 7.0
+    lib = torch.softmax(torch.from_numpy(X) @ torch.from_numpy(Wg), dim=1).numpy()
+    np.testing.assert_allclose(ref.gate(X, Wg, np.float64), lib, rtol=1e-12, atol=1e-15)
+
+
+def test_gate_widens_bf16_exactly():
+    r = _rng(3)
+    Xf = r.standard_normal((8, 16)).astype(np.float32)
+    Wf = r.standard_normal((16, 4)).astype(np.float32)
+    Xb, Wb = wl.f32_to_bf16_bits(Xf), wl.f32_to_bf16_bits(Wf)
+    S_bits = ref.gate(Xb, Wb, np.float64)
+    S_wide = ref.gate(wl.bf16_bits_to_f32(Xb), wl.bf16_bits_to_f32(Wb), np.float64)
+    assert (S_bits == S_wide).all()
+    # 1.0 and -2.5 have exact bf16 forms
+    assert (ref.widen(np.array([0x3F80, 0xC020], np.uint16)) == np.array([1.0, -2.5])).all()
+
+
+def _brute_topk(col, k):
+    """Pure-Python selection: k times, take the largest remaining, lowest index on ties."""
+    taken = []
+    alive = list(range(len(col)))
+    for _ in range(k):
+        best = alive[0]
+        for t in alive[1:]:
+            if col[t] > col[best]:
+                best = t
+        taken.append(best)
+        alive.remove(best)
+    return taken
+
+
+def test_topk_handworked(golden):
+    S = np.array(golden["S"], dtype=np.float32)
+    G, I = ref.topk_tokens(S, golden["k"])
+    assert I.tolist() == golden["I"]
+    assert G.tolist() == golden["G"]
+    counts = np.bincount(I.ravel(), minlength=golden["n"])
+    assert counts.tolist() == golden["experts_per_token"]
+
+
+@pytest.mark.parametrize("seed,n,e,k,levels", [(0, 17, 3, 5, 0), (1, 32, 4, 32, 0),
+                                              (2, 29, 5, 7, 4), (3, 24, 2, 1, 3)])
+def test_topk_against_brute_force(seed, n, e, k, levels):
+    r = _rng(seed)
+    S = r.random((n, e)).astype(np.float32)
+    if levels:   # quantise so that many scores tie, also across the k-th place
+        S = (np.floor(S * levels) / levels).astype(np.float32)
+    G, I = ref.topk_tokens(S, k)
+    for i in range(e):
+        expect = _brute_topk(S[:, i].tolist(), k)
+        assert I[i].tolist() == expect
+        assert (G[i] == S[expect, i]).all()
+
+
+def test_topk_invariants_and_lexsort():
+    r = _rng(5)
+    n, e, k = 512, 8, 96
+    S = ref.gate(r.standard_normal((n, 24)), r.standard_normal((24, e)))
+    S[::7, :] = S[3, :]          # plant ties
+    G, I = ref.topk_tokens(S, k)
+    assert I.dtype == np.int32 and G.dtype == np.float32
+    for i in range(e):
+        ids = I[i]
+        assert len(set(ids.tolist())) == k and ids.min() >= 0 and ids.max() < n   # k distinct tokens
+        assert (G[i] == S[ids, i]).all()                                            # raw scores, bitwise
+        unsel = np.setdiff1d(np.arange(n), ids)
+        lo = G[i].min()
+        assert lo >= S[unsel, i].max()
+        # an unselected token tying with the threshold must have a higher index
+        # than every selected token at the threshold
+        tied_out = unsel[S[unsel, i] == lo]
+        tied_in = ids[G[i] == lo]
+        if tied_out.size:
+            assert tied_out.min() > tied_in.max()
+        # independent library ordering: last key is primary in lexsort
+        order = np.lexsort((np.arange(n), -S[:, i].astype(np.float64)))
+        assert (order[:k] == ids).all()
+    assert I.size == e * k                                                          # sum of buckets = n*c
+
+
+def test_topk_all_ties_and_full_capacity():
+    n, e = 40, 4
+    S = np.full((n, e), 0.25, np.float32)
+    G, I = ref.topk_tokens(S, 10)
+    assert (I == np.arange(10)[None, :]).all() and (G == 0.25).all()
+    r = _rng(6)
+    S = r.random((n, e)).astype(np.float32)
+    G, I = ref.topk_tokens(S, n)                  # k = n: a permutation, sorted by score
+    for i in range(e):
+        assert sorted(I[i].tolist()) == list(range(n))
+        assert (np.diff(G[i]) <= 0).all()
+
+
+# --------------------------------------------------------------- Eq. 3 ------
+def _onehot(I, n):
+    e, k = I.shape
+    P = np.zeros((e, k, n))
+    for i in range(e):
+        for j in range(k):
+            P[i, j, I[i, j]] = 1.0
+    return P
+
+
+def test_dispatch_equals_onehot_einsum():
+    r = _rng(7)
+    n, d, e, k = 12, 5, 3, 4
+    X = r.standard_normal((n, d))
+    I = np.stack([r.permutation(n)[:k] for _ in range(e)]).astype(np.int32)
+    X_in = ref.dispatch(X, I)
+    np.testing.assert_array_equal(X_in, np.einsum("ikn,nd->ikd", _onehot(I, n), X))
+    # storage type and bits are kept
+    Xb = wl.f32_to_bf16_bits(X.astype(np.float32))
+    assert ref.dispatch(Xb, I).dtype == np.uint16
+    assert (ref.dispatch(Xb, I)[2, 1] == Xb[I[2, 1]]).all()
+
+
+def test_ffn_handworked(golden):
+    g = golden["ffn_example"]
+    for act, expect in [(ref.ACT_GELU, g["X_e"]), (ref.ACT_RELU, 3.0), (ref.ACT_IDENTITY, 3.0)]:
+        out = ref.expert_ffn(np.array([[[g["x"]]]]), np.array([[[g["W1"]]]]), np.array([[[g["W2"]]]]), act)
+        assert out.shape == (1, 1, 1)
+        assert abs(out[0, 0, 0] - expect) < 1e-15
+    # negative pre-activation: ReLU clips, GeLU(-1) = -(1 - Phi(1))
+    out = ref.expert_ffn(np.array([[[-2.0]]]), np.array([[[0.5]]]), np.array([[[3.0]]]), ref.ACT_RELU)
+    assert out[0, 0, 0] == 0.0
+    out = ref.expert_ffn(np.array([[[-2.0]]]), np.array([[[0.5]]]), np.array([[[3.0]]]), ref.ACT_GELU)
+    assert abs(out[0, 0, 0] + 3.0 * (1.0 - g["gelu_of_1"])) < 1e-15
+
+
+def test_ffn_against_library_and_shapes():
+    r = _rng(8)
+    e, k, d, d_ff = 3, 7, 6, 10               # all different: a transposed operand cannot pass
+    X_in = r.standard_normal((e, k, d))
+    W1 = r.standard_normal((e, d, d_ff))
+    W2 = r.standard_normal((e, d_ff, d))
+    tX, tW1, tW2 = map(torch.from_numpy, (X_in, W1, W2))
+    for act, fn in [(ref.ACT_GELU, lambda a: torch.nn.functional.gelu(a, approximate="none")),
+                    (ref.ACT_RELU, torch.relu), (ref.ACT_IDENTITY, lambda a: a)]:
+        lib = torch.bmm(fn(torch.bmm(tX, tW1)), tW2).numpy()
+        np.testing.assert_allclose(ref.expert_ffn(X_in, W1, W2, act), lib, rtol=1e-12, atol=1e-13)
+    # per-element definition on one entry
+    i, j, t = 1, 4, 2
+    a = [sum(X_in[i, j, u] * W1[i, u, f] for u in range(d)) for f in range(d_ff)]
+    h = [0.5 * v * (1.0 + math.erf(v / math.sqrt(2.0))) for v in a]
+    val = sum(h[f] * W2[i, f, t] for f in range(d_ff))
+    assert abs(ref.expert_ffn(X_in, W1, W2, ref.ACT_GELU)[i, j, t] - val) < 1e-12
+    # identity activation is linear in X_in
+    lin = ref.expert_ffn(2.0 * X_in, W1, W2, ref.ACT_IDENTITY)
+    np.testing.assert_allclose(lin, 2.0 * ref.expert_ffn(X_in, W1, W2, ref.ACT_IDENTITY), rtol=1e-12)
+
+
+def test_activation_grad_by_central_difference():
+    a = np.linspace(-4.0, 4.0, 41) + 0.013
+    h = 1e-6
+    for act in (ref.ACT_GELU, ref.ACT_RELU, ref.ACT_IDENTITY):
+        fd = (ref.activation(a + h, act) - ref.activation(a - h, act)) / (2 * h)
+        np.testing.assert_allclose(ref.activation_grad(a, act), fd, atol=1e-8)
+
+
+# --------------------------------------------------------------- Eq. 4 ------
+def test_combine_equals_dense_einsum_and_counts():
+    r = _rng(9)
+    n, d, e, k = 14, 4, 5, 6
+    X_e = r.standard_normal((e, k, d))
+    G = r.random((e, k)).astype(np.float32)
+    I = np.stack([r.permutation(n)[:k] for _ in range(e)]).astype(np.int32)
+    out = ref.combine(X_e, G, I, n)
+    dense = np.einsum("ijl,ij,ijd->ld", _onehot(I, n), G.astype(np.float64), X_e)
+    np.testing.assert_allclose(out, dense, rtol=1e-13, atol=1e-14)
+    counts = np.bincount(I.ravel(), minlength=n)
+    assert counts.sum() == e * k and counts.max() <= e
+    assert (np.abs(out[counts == 0]).sum(axis=1) == 0).all()       # unrouted tokens: zero rows
+
+
+def test_layer_identity_experts_closed_form(golden):
+    # hand-worked: X_out[l] = (sum of the selected scores of token l) * X[l]
+    S = np.array(golden["S"], dtype=np.float32)
+    G, I = ref.topk_tokens(S, golden["k"])
+    X = _rng(10).standard_normal((golden["n"], 3))
+    out = ref.combine(ref.dispatch(X, I), G, I, golden["n"])
+    np.testing.assert_allclose(out, np.array(golden["identity_expert_row_scale"])[:, None] * X, rtol=1e-15)
+    # same closed form through forward() on random data
+    r = _rng(11)
+    n, d, e, c = 48, 8, 6, 2.0
+    X = r.standard_normal((n, d)).astype(np.float32)
+    Wg = r.standard_normal((d, e)).astype(np.float32)
+    f = ref.forward(X, Wg, None, None, c, ref.ACT_IDENTITY)
+    scale = np.zeros(n)
+    for i in range(e):
+        for j in range(f["k"]):
+            scale[f["I"][i, j]] += float(f["S"][f["I"][i, j], i])
+    np.testing.assert_allclose(f["X_out"], scale[:, None] * X.astype(np.float64), rtol=1e-13, atol=1e-15)
+    counts = np.bincount(f["I"].ravel(), minlength=n)
+    assert counts.sum() == int(n * c) and 0 <= counts.min() and counts.max() <= e
+
+
+def _dense_ffn(x, W1, W2, act):
+    t = torch.from_numpy(x) @ torch.from_numpy(W1)
+    t = torch.nn.functional.gelu(t) if act == ref.ACT_GELU else torch.relu(t)
+    return (t @ torch.from_numpy(W2)).numpy()
+
+
+def test_layer_one_expert_is_dense_ffn():
+    # e = 1, c = 1: every token goes through the single expert with weight 1
+    r = _rng(12)
+    n, d, d_ff = 20, 6, 9
+    X = r.standard_normal((n, d))
+    Wg = r.standard_normal((d, 1))
+    W1 = r.standard_normal((1, d, d_ff))
+    W2 = r.standard_normal((1, d_ff, d))
+    f = ref.forward(X, Wg, W1, W2, 1.0, ref.ACT_GELU)
+    assert f["k"] == n and (f["I"][0] == np.arange(n)).all()       # all scores 1.0: ties by index
+    np.testing.assert_allclose(f["X_out"], _dense_ffn(X, W1[0], W2[0], ref.ACT_GELU), rtol=1e-12, atol=1e-13)
+
+
+def test_layer_full_capacity_is_dense_soft_mixture():
+    # c = e: k = n, every expert processes every token; X_out = sum_i S[:,i] * FFN_i(X)
+    r = _rng(13)
+    n, d, d_ff, e = 10, 5, 7, 3
+    X = r.standard_normal((n, d)).astype(np.float32)
+    Wg = r.standard_normal((d, e)).astype(np.float32)
+    W1 = r.standard_normal((e, d, d_ff)).astype(np.float32)
+    W2 = r.standard_normal((e, d_ff, d)).astype(np.float32)
+    f = ref.forward(X, Wg, W1, W2, float(e), ref.ACT_RELU)
+    S = f["S"].astype(np.float64)
+    expect = sum(S[:, i:i + 1] * _dense_ffn(X.astype(np.float64), W1[i].astype(np.float64),
+                                            W2[i].astype(np.float64), ref.ACT_RELU) for i in range(e))
+    np.testing.assert_allclose(f["X_out"], expect, rtol=1e-12, atol=1e-13)
+
+
+def test_layer_zero_gate_closed_form():
+    # Wg = 0: all scores tie at 1/e, every expert takes tokens 0..k-1;
+    # X_out[l] = (1/e) sum_i FFN_i(X[l]) for l < k and 0 beyond
+    r = _rng(14)
+    n, d, d_ff, e, c = 16, 4, 6, 4, 2.0
+    X = r.standard_normal((n, d)).astype(np.float32)
+    W1 = r.standard_normal((e, d, d_ff)).astype(np.float32)
+    W2 = r.standard_normal((e, d_ff, d)).astype(np.float32)
+    f = ref.forward(X, np.zeros((d, e), np.float32), W1, W2, c, ref.ACT_GELU)
+    k = f["k"]
+    assert k == 8 and (f["I"] == np.arange(k)[None, :]).all()
+    mean = sum(_dense_ffn(X[:k].astype(np.float64), W1[i].astype(np.float64), W2[i].astype(np.float64),
+                          ref.ACT_GELU) for i in range(e)) * float(np.float32(1.0 / e))
+    np.testing.assert_allclose(f["X_out"][:k], mean, rtol=1e-12, atol=1e-13)
+    assert (f["X_out"][k:] == 0).all()
+
+
+def test_layer_expert_permutation_invariance():
+    r = _rng(15)
+    n, d, d_ff, e = 24, 6, 8, 4
+    X = r.standard_normal((n, d)).astype(np.float32)
+    Wg = r.standard_normal((d, e)).astype(np.float32)
+    W1 = r.standard_normal((e, d, d_ff)).astype(np.float32)
+    W2 = r.standard_normal((e, d_ff, d)).astype(np.float32)
+    p = np.array([2, 0, 3, 1])
+    a = ref.forward(X, Wg, W1, W2, 2.0, ref.ACT_GELU)
+    b = ref.forward(X, Wg[:, p], W1[p], W2[p], 2.0, ref.ACT_GELU)
+    np.testing.assert_allclose(a["X_out"], b["X_out"], rtol=1e-12, atol=1e-14)
+    assert (a["I"][p] == b["I"]).all()
+
+
+# ------------------------------------------------------------- backward -----
+def _loss_fixed_selection(X, Wg, W1, W2, act, I, dY):
+    """<dY, X_out> with the selection I held constant, built from the oracle's forward pieces."""
+    S = ref.gate(X, Wg, out_dtype=np.float64)
+    G = np.stack([S[I[i], i] for i in range(I.shape[0])])
+    X_e = ref.expert_ffn(ref.dispatch(X, I), W1, W2, act)
+    return float((ref.combine(X_e, G, I, X.shape[0]) * dY).sum())
+
+
+def _small_problem(seed, act):
+    r = _rng(seed)
+    n, d, d_ff, e, c = 12, 5, 7, 3, 2.0
+    X = r.standard_normal((n, d))
+    Wg = r.standard_normal((d, e))
+    W1 = r.standard_normal((e, d, d_ff)) / math.sqrt(d)
+    W2 = r.standard_normal((e, d_ff, d)) / math.sqrt(d_ff)
+    dY = r.standard_normal((n, d))
+    S64 = ref.gate(X, Wg, out_dtype=np.float64)
+    k = ref.capacity(n, c, e)
+    _, I = ref.topk_tokens(S64.astype(np.float32), k)
+    G64 = np.stack([S64[I[i], i] for i in range(e)])
+    return X, Wg, W1, W2, dY, S64, G64, I
+
+
+@pytest.mark.parametrize("act", [ref.ACT_GELU, ref.ACT_IDENTITY])
+def test_backward_against_central_differences(act):
+    X, Wg, W1, W2, dY, S, G, I = _small_problem(21, act)
+    g = ref.backward(X, Wg, W1, W2, act, S, G, I, dY)
+    h = 1e-6
+    r = _rng(22)
+    for name, arr in (("dX", X), ("dWg", Wg), ("dW1", W1), ("dW2", W2)):
+        for _ in range(12):
+            idx = tuple(int(r.integers(0, s)) for s in arr.shape)
+            old = arr[idx]
+            arr[idx] = old + h
+            lp = _loss_fixed_selection(X, Wg, W1, W2, act, I, dY)
+            arr[idx] = old - h
+            lm = _loss_fixed_selection(X, Wg, W1, W2, act, I, dY)
+            arr[idx] = old
+            fd = (lp - lm) / (2 * h)
+            assert abs(fd - g[name][idx]) <= 1e-6 * max(1.0, abs(fd)), (name, idx, fd, g[name][idx])
+
+
+def test_backward_against_autograd_restatement():
+    act = ref.ACT_GELU
+    X, Wg, W1, W2, dY, S, G, I = _small_problem(23, act)
+    g = ref.backward(X, Wg, W1, W2, act, S, G, I, dY)
+    tX, tWg, tW1, tW2 = (torch.tensor(a, requires_grad=True) for a in (X, Wg, W1, W2))
+    tS = torch.softmax(tX @ tWg, dim=1)
+    out = torch.zeros_like(tX)
+    for i in range(I.shape[0]):
+        idx = torch.from_numpy(I[i].astype(np.int64))
+        xin = tX.index_select(0, idx)
+        xe = torch.nn.functional.gelu(xin @ tW1[i]) @ tW2[i]
+        out = out.index_add(0, idx, tS[idx, i][:, None] * xe)
+    (out * torch.from_numpy(dY)).sum().backward()
+    for name, t in (("dX", tX), ("dWg", tWg), ("dW1", tW1), ("dW2", tW2)):
+        np.testing.assert_allclose(g[name], t.grad.numpy(), rtol=1e-10, atol=1e-12)
+
+
+def test_backward_one_expert_is_dense_ffn_gradient():
+    r = _rng(24)
+    n, d, d_ff = 9, 4, 6
+    X = r.standard_normal((n, d))
+    Wg = r.standard_normal((d, 1))
+    W1 = r.standard_normal((1, d, d_ff))
+    W2 = r.standard_normal((1, d_ff, d))
+    dY = r.standard_normal((n, d))
+    f = ref.forward(X, Wg, W1, W2, 1.0, ref.ACT_RELU)
+    g = ref.backward(X, Wg, W1, W2, ref.ACT_RELU, f["S"], f["G"], f["I"], dY)
+    tX, tW1, tW2 = (torch.tensor(a, requires_grad=True) for a in (X, W1[0], W2[0]))
+    ((torch.relu(tX @ tW1) @ tW2) * torch.from_numpy(dY)).sum().backward()
+    np.testing.assert_allclose(g["dX"], tX.grad.numpy(), rtol=1e-12, atol=1e-13)
+    np.testing.assert_allclose(g["dW1"][0], tW1.grad.numpy(), rtol=1e-12, atol=1e-13)
+    np.testing.assert_allclose(g["dW2"][0], tW2.grad.numpy(), rtol=1e-12, atol=1e-13)
+    assert np.abs(g["dWg"]).max() < 1e-12            # a softmax over one expert has no gradient
+
+
+# ------------------------------------------------------------- workloads ----
+def test_workload_generators_are_seeded_and_shaped():
+    w = wl.WORKLOADS["cfg1"]
+    a, b = wl.make_inputs(w), wl.make_inputs(w)
+    assert all((a[key] == b[key]).all() for key in a)
+    assert a["X"].shape == (256, 64) and a["Wg"].shape == (64, 8)
+    assert a["W1"].shape == (8, 64, 256) and a["W2"].shape == (8, 256, 64)
+    assert abs(a["Wg"].std() - 1 / 8) < 0.01 and abs(a["W2"].std() - 1 / 16) < 0.01
+    s = wl.scaled(wl.WORKLOADS["cfg5"], n=2048, d=64, e=8)
+    t = wl.make_inputs(s)
+    assert t["X"].dtype == np.uint16 and "W1" not in t and len(t["skew_rows"]) == 20
+    # bf16 rounding: nearest-even on a few exact cases
+    bits = wl.f32_to_bf16_bits(np.array([1.0, 1.00390625, 1.01171875, -2.5], np.float32))
+    assert bits.tolist() == [0x3F80, 0x3F80, 0x3F82, 0xC020]
