@@ -1,0 +1,154 @@
+/*
+ * ec_moe.h -- C ABI of the expert-choice Mixture-of-Experts layer for AMD
+ * Instinct MI355X (gfx950 / CDNA4).
+ *
+ * The layer follows "Mixture-of-Experts with Expert Choice Routing"
+ * (arXiv 2202.09368), Sec. 3.2:
+ *   Eq. 1  k = n*c/e                      bucket size of every expert
+ *   Eq. 2  S = Softmax(X.Wg);  G, I = TopK(S^T, k)
+ *   Eq. 3  X_in = P.X (P = Onehot(I));  X_e[i] = act(X_in[i].W1[i]).W2[i]
+ *   Eq. 4  X_out[l,:] = sum_{i,j} P[i,j,l] G[i,j] X_e[i,j,:]
+ * Notation is the paper's: n tokens, d model width, e experts, c capacity
+ * factor, k tokens per expert, d_ff expert hidden width (the paper's d').
+ *
+ * General conventions (all entry points)
+ *  - Every tensor pointer is a DEVICE pointer owned by the caller, dense,
+ *    row-major, no strides, 16-byte aligned.  The library never allocates or
+ *    frees device memory; scratch comes from the caller's workspace `ws`
+ *    (device pointer, 256-byte aligned, at least ec_moe_workspace_bytes()).
+ *  - Calls are asynchronous on `stream` (a hipStream_t passed as void*, NULL =
+ *    the default stream).  Nothing synchronises.  Outputs are fully
+ *    overwritten; no output needs to be cleared beforehand.
+ *  - Sizes are int64_t; token indices int32_t (n < 2^31); S and G are always
+ *    float.  `dtype` (ec_dtype) is the storage type of X, Wg, W1, W2, X_in,
+ *    X_e, X_out: EC_F32 or EC_BF16 (bf16 operands, fp32 accumulation).
+ *  - With EC_BF16, d and d_ff must be multiples of 8 (16-byte rows).
+ *  - Every function returns an ec_status.  Arguments are validated on the
+ *    host before anything is launched; on error nothing has been enqueued.
+ *    EC_ERR_HIP means a launch failed: ec_moe_last_hip_error() returns the
+ *    hipError_t of the calling thread's last failure.
+ *  - Inputs must be finite; NaN/Inf give unspecified routing.
+ *  - Calls that share a workspace must be ordered on one stream.
+ */
+#ifndef EC_MOE_H
+#define EC_MOE_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    EC_OK = 0,
+    EC_ERR_INVALID_ARG = -1, /* null pointer, non-positive size, k outside [1,n], bad enum, misaligned */
+    EC_ERR_WORKSPACE = -2,   /* workspace null or smaller than required */
+    EC_ERR_HIP = -3,         /* a HIP call failed; see ec_moe_last_hip_error() */
+    EC_ERR_UNSUPPORTED = -4  /* valid request outside what the kernels cover */
+} ec_status;
+
+typedef enum { EC_F32 = 0, EC_BF16 = 1 } ec_dtype;
+typedef enum { EC_ACT_RELU = 0, EC_ACT_GELU = 1 /* exact erf form */, EC_ACT_IDENTITY = 2 } ec_act;
+
+/* Largest number of experts the routing kernels accept. */
+#define EC_MOE_MAX_EXPERTS 1024
+
+/* Host only.  Sec. 3.2, Eq. 1: *k = floor(n*c/e), evaluated in double.
+ * EC_ERR_INVALID_ARG if n, e <= 0, c <= 0, k == NULL, or k would fall outside [1, n]. */
+int ec_moe_capacity(int64_t n, int64_t e, double c, int64_t* k);
+
+/* Host only.  Bytes of workspace sufficient for ANY entry point below at these
+ * sizes (d_ff may be 0 for identity experts; with_backward != 0 adds what
+ * ec_moe_backward needs).  Returns 0 for invalid sizes. */
+size_t ec_moe_workspace_bytes(int64_t n, int64_t d, int64_t e, int64_t k, int64_t d_ff,
+                              int dtype, int with_backward);
+
+/* Sec. 3.2, Eq. 2 (first line) and Sec. 3.4: token-to-expert affinity scores.
+ *   Z = X.Wg with fp32 accumulation; S[l,:] = softmax over the e experts of
+ *   Z[l,:] (max-subtracted, fp32).
+ * X [n,d] and Wg [d,e] in `dtype`.  S [n,e] and St [e,n] (the transpose, the
+ * layout ec_moe_topk_tokens reads) are float outputs; either may be NULL but
+ * not both.  e <= EC_MOE_MAX_EXPERTS. */
+int ec_moe_gate(const void* X, const void* Wg, float* S, float* St,
+                int64_t n, int64_t d, int64_t e, int dtype,
+                void* ws, size_t ws_bytes, void* stream);
+
+/* Sec. 3.2, Eq. 2 (second line): G, I = TopK(S^T, k).  For every expert i the k
+ * largest scores over the n tokens.  St [e,n] float, all values >= 0 (softmax
+ * output; negative or NaN values are outside the contract).
+ * I [e,k] int32: token indices; G [e,k] float: G[i,j] = St[i, I[i,j]] bit for bit.
+ * A bucket is ordered by descending score; equal scores by ascending token
+ * index; the same rule decides which of several equal scores are admitted at
+ * the k-th place.  The result is therefore unique.  1 <= k <= n. */
+int ec_moe_topk_tokens(const float* St, int64_t n, int64_t e, int64_t k,
+                       float* G, int32_t* I, void* ws, size_t ws_bytes, void* stream);
+
+/* Sec. 3.2, Eq. 3 (first line), the "shuffle" stage of Sec. 3.4:
+ * X_in[i,j,:] = X[I[i,j],:].  X [n,d], X_in [e,k,d] in `dtype`; a bit-exact
+ * copy.  Every I[i,j] must lie in [0,n) (not checked on the device). */
+int ec_moe_dispatch(const void* X, const int32_t* I, void* Xin,
+                    int64_t n, int64_t d, int64_t e, int64_t k, int dtype, void* stream);
+
+/* Sec. 3.2, Eq. 3 (second line): X_e[i] = act(X_in[i].W1[i]).W2[i], no bias.
+ * X_in [e,k,d], W1 [e,d,d_ff], W2 [e,d_ff,d] (the paper's W2[i]^T stored
+ * untransposed), X_e [e,k,d], all in `dtype`.  EC_BF16: fp32 accumulation, the
+ * hidden activations H = act(A) are rounded to bf16 between the two products,
+ * X_e is rounded to bf16.  A_save / H_save: optional [e,k,d_ff] outputs in
+ * `dtype` (pre-activation A = X_in.W1 and H), kept for ec_moe_backward; NULL to
+ * skip.  act = EC_ACT_IDENTITY is a plain two-matrix product. */
+int ec_moe_expert_ffn(const void* Xin, const void* W1, const void* W2, void* Xe,
+                      void* A_save, void* H_save,
+                      int64_t e, int64_t k, int64_t d, int64_t d_ff, int act, int dtype,
+                      void* ws, size_t ws_bytes, void* stream);
+
+/* Sec. 3.2, Eq. 4, the "unshuffle" stage of Sec. 3.4:
+ * X_out[l,:] = sum over the (i,j) with I[i,j] = l of G[i,j] * X_e[i,j,:], and 0
+ * for tokens no expert selected.  Deterministic: a token's contributions are
+ * added in ascending expert order in fp32 and rounded once to `dtype`; no
+ * floating-point atomics.  A token may appear at most once per expert (true of
+ * any TopK output) and every I[i,j] must lie in [0,n).
+ * X_e [e,k,d], G [e,k], I [e,k], X_out [n,d].  e <= EC_MOE_MAX_EXPERTS. */
+int ec_moe_combine(const void* Xe, const float* G, const int32_t* I, void* Xout,
+                   int64_t n, int64_t d, int64_t e, int64_t k, int dtype,
+                   void* ws, size_t ws_bytes, void* stream);
+
+/* Sec. 3.2, Eq. 1-4 in one call on one stream: gate, TopK over tokens,
+ * dispatch, expert FFN, combine.  k = floor(n*c/e) as in ec_moe_capacity.
+ * W1 = W2 = NULL with act = EC_ACT_IDENTITY runs identity experts (routing
+ * only: X_e = X_in); d_ff is then ignored.
+ * Optional outputs, each NULL to skip: S_out [n,e], G_out [e,k], I_out [e,k]
+ * (int32), Xin_out [e,k,d], A_out / H_out [e,k,d_ff], Xe_out [e,k,d] -- the
+ * tensors ec_moe_backward consumes.  X_out [n,d] is required. */
+int ec_moe_forward(const void* X, const void* Wg, const void* W1, const void* W2, double c,
+                   void* Xout, float* S_out, float* G_out, int32_t* I_out,
+                   void* Xin_out, void* A_out, void* H_out, void* Xe_out,
+                   int64_t n, int64_t d, int64_t e, int64_t d_ff, int act, int dtype,
+                   void* ws, size_t ws_bytes, void* stream);
+
+/* Gradient of <dY, X_out> through Eq. 2-4 with the selection I held constant
+ * and the gate values G differentiable (Sec. 3.4: the gating network is
+ * trained through the top-k function).  Inputs: dY [n,d] and the forward's
+ * X, Wg, W1, W2, S [n,e], G, I [e,k], X_in [e,k,d], A, H [e,k,d_ff], X_e [e,k,d].
+ * Outputs: dX [n,d] in `dtype`; dWg [d,e], dW1 [e,d,d_ff], dW2 [e,d_ff,d] float.
+ * ws must come from ec_moe_workspace_bytes(..., with_backward = 1). */
+int ec_moe_backward(const void* dY, const void* X, const void* Wg, const void* W1, const void* W2,
+                    const float* S, const float* G, const int32_t* I,
+                    const void* Xin, const void* A, const void* H, const void* Xe,
+                    void* dX, float* dWg, float* dW1, float* dW2,
+                    int64_t n, int64_t d, int64_t e, int64_t k, int64_t d_ff, int act, int dtype,
+                    void* ws, size_t ws_bytes, void* stream);
+
+/* hipError_t (as int) of the calling thread's most recent EC_ERR_HIP, else 0. */
+int ec_moe_last_hip_error(void);
+
+/* Static, human-readable name of an ec_status value. */
+const char* ec_moe_status_string(int status);
+
+/* Library version, "major.minor". */
+const char* ec_moe_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* EC_MOE_H */

@@ -1,0 +1,213 @@
+// C ABI of libec_moe.so: argument validation, workspace carving, and the
+// forward chain gate -> TopK over tokens -> dispatch -> expert FFN -> combine
+// (Sec. 3.2, Eq. 1-4).  All arithmetic lives in the kernels of the other files.
+#include <cmath>
+
+#include "ec_common.h"
+
+namespace ecmoe {
+
+static thread_local int g_last_hip_error = 0;
+void set_last_hip_error(hipError_t err) { g_last_hip_error = (int)err; }
+
+size_t topk_ws_bytes(int64_t n, int64_t e, int64_t k);  // topk.hip
+
+WsLayout ws_layout(int64_t n, int64_t d, int64_t e, int64_t k, int64_t d_ff, int dtype, int with_backward) {
+    WsLayout L;
+    const size_t es = elem_size(dtype);
+    const size_t e_pad = (size_t)ceil_div(e, 32) * 32;
+    size_t off = 0;
+    auto take = [&](size_t bytes) {
+        size_t at = off;
+        off = align_up(off + bytes, 256);
+        return at;
+    };
+    L.wgt = take(e_pad * (size_t)d * 2);
+    L.st = take((size_t)e * n * 4);
+    L.g = take((size_t)e * k * 4);
+    L.i = take((size_t)e * k * 4);
+    L.xin = take((size_t)e * k * d * es);
+    L.h = take((size_t)e * k * (size_t)(d_ff > 0 ? d_ff : 0) * es);
+    L.xe = take((size_t)e * k * d * es);
+    L.bitmap = take((size_t)n * (size_t)ceil_div(e, 32) * 4);
+    L.offsets = take((size_t)(n + 1) * 4);
+    L.inv = take((size_t)e * k * 4);
+    L.sortkeys = take(topk_ws_bytes(n, e, k));
+    L.bwd = off;
+    if (with_backward) take(bwd_ws_bytes(n, d, e, k, d_ff, dtype));
+    L.total = off;
+    return L;
+}
+
+static bool sizes_ok(int64_t n, int64_t d, int64_t e, int64_t k) {
+    return n > 0 && d > 0 && e > 0 && k >= 1 && k <= n && n < (int64_t)1 << 31 && d < (int64_t)1 << 31 &&
+           e <= EC_MOE_MAX_EXPERTS && e * k < (int64_t)1 << 31;
+}
+static bool dtype_ok(int dtype) { return dtype == EC_F32 || dtype == EC_BF16; }
+static bool act_ok(int act) { return act == EC_ACT_RELU || act == EC_ACT_GELU || act == EC_ACT_IDENTITY; }
+static bool width_ok(int64_t w, int dtype) { return dtype != EC_BF16 || (w % 8) == 0; }
+template <typename... P>
+static bool all_aligned(P... ptrs) {
+    bool ok = true;
+    const void* list[] = {ptrs...};
+    for (const void* q : list) ok = ok && (q == nullptr || aligned16(q));
+    return ok;
+}
+static bool ws_ok(const void* ws, size_t ws_bytes, size_t need) {
+    return need == 0 || (ws != nullptr && ws_bytes >= need && (reinterpret_cast<uintptr_t>(ws) & 255u) == 0);
+}
+static unsigned char* at(void* ws, size_t off) { return static_cast<unsigned char*>(ws) + off; }
+
+}  // namespace ecmoe
+
+using namespace ecmoe;
+
+extern "C" {
+
+int ec_moe_capacity(int64_t n, int64_t e, double c, int64_t* k) {
+    if (k == nullptr || n <= 0 || e <= 0 || !(c > 0.0) || !std::isfinite(c)) return EC_ERR_INVALID_ARG;
+    double kd = std::floor((double)n * c / (double)e);
+    if (!(kd >= 1.0) || kd > (double)n) return EC_ERR_INVALID_ARG;
+    *k = (int64_t)kd;
+    return EC_OK;
+}
+
+size_t ec_moe_workspace_bytes(int64_t n, int64_t d, int64_t e, int64_t k, int64_t d_ff, int dtype,
+                              int with_backward) {
+    if (!sizes_ok(n, d, e, k) || d_ff < 0 || !dtype_ok(dtype)) return 0;
+    return ws_layout(n, d, e, k, d_ff, dtype, with_backward).total;
+}
+
+int ec_moe_gate(const void* X, const void* Wg, float* S, float* St, int64_t n, int64_t d, int64_t e, int dtype,
+                void* ws, size_t ws_bytes, void* stream) {
+    if (!X || !Wg || (!S && !St) || n <= 0 || d <= 0 || e <= 0 || e > EC_MOE_MAX_EXPERTS || n >= (int64_t)1 << 31 ||
+        !dtype_ok(dtype) || !all_aligned(X, Wg, S, St))
+        return EC_ERR_INVALID_ARG;
+    // only the transposed, padded copy of Wg lives in the workspace
+    const size_t need = dtype == EC_BF16 ? align_up((size_t)ceil_div(e, 32) * 32 * (size_t)d * 2, 256) : 0;
+    if (!ws_ok(ws, ws_bytes, need)) return EC_ERR_WORKSPACE;
+    return launch_gate(X, Wg, S, St, n, d, e, dtype, need ? ws : nullptr, (hipStream_t)stream);
+}
+
+int ec_moe_topk_tokens(const float* St, int64_t n, int64_t e, int64_t k, float* G, int32_t* I, void* ws,
+                       size_t ws_bytes, void* stream) {
+    if (!St || !G || !I || !sizes_ok(n, 1, e, k) || !all_aligned(St, G, I)) return EC_ERR_INVALID_ARG;
+    const size_t need = topk_ws_bytes(n, e, k);
+    if (!ws_ok(ws, ws_bytes, need)) return EC_ERR_WORKSPACE;
+    return launch_topk(St, n, e, k, G, I, need ? (unsigned long long*)ws : nullptr, (hipStream_t)stream);
+}
+
+int ec_moe_dispatch(const void* X, const int32_t* I, void* Xin, int64_t n, int64_t d, int64_t e, int64_t k,
+                    int dtype, void* stream) {
+    if (!X || !I || !Xin || !sizes_ok(n, d, e, k) || !dtype_ok(dtype) || !width_ok(d, dtype) ||
+        !all_aligned(X, I, Xin))
+        return EC_ERR_INVALID_ARG;
+    return launch_dispatch(X, I, Xin, n, d, e, k, dtype, (hipStream_t)stream);
+}
+
+int ec_moe_expert_ffn(const void* Xin, const void* W1, const void* W2, void* Xe, void* A_save, void* H_save,
+                      int64_t e, int64_t k, int64_t d, int64_t d_ff, int act, int dtype, void* ws, size_t ws_bytes,
+                      void* stream) {
+    if (!Xin || !W1 || !W2 || !Xe || e <= 0 || k <= 0 || d <= 0 || d_ff <= 0 || e > EC_MOE_MAX_EXPERTS ||
+        k >= (int64_t)1 << 31 || d >= (int64_t)1 << 31 || d_ff >= (int64_t)1 << 31 || !dtype_ok(dtype) ||
+        !act_ok(act) || !width_ok(d, dtype) || !width_ok(d_ff, dtype) ||
+        !all_aligned(Xin, W1, W2, Xe, A_save, H_save))
+        return EC_ERR_INVALID_ARG;
+    void* H = H_save;
+    if (!H) {
+        const size_t need = align_up((size_t)e * k * d_ff * elem_size(dtype), 256);
+        if (!ws_ok(ws, ws_bytes, need)) return EC_ERR_WORKSPACE;
+        H = ws;
+    }
+    return launch_ffn(Xin, W1, W2, Xe, A_save, H, e, k, d, d_ff, act, dtype, (hipStream_t)stream);
+}
+
+int ec_moe_combine(const void* Xe, const float* G, const int32_t* I, void* Xout, int64_t n, int64_t d, int64_t e,
+                   int64_t k, int dtype, void* ws, size_t ws_bytes, void* stream) {
+    if (!Xe || !G || !I || !Xout || !sizes_ok(n, d, e, k) || !dtype_ok(dtype) || !width_ok(d, dtype) ||
+        !all_aligned(Xe, G, I, Xout))
+        return EC_ERR_INVALID_ARG;
+    // token-major index: bitmap, offsets, inverse list
+    const size_t bm = align_up((size_t)n * (size_t)ceil_div(e, 32) * 4, 256);
+    const size_t of = align_up((size_t)(n + 1) * 4, 256);
+    const size_t iv = align_up((size_t)e * k * 4, 256);
+    if (!ws_ok(ws, ws_bytes, bm + of + iv)) return EC_ERR_WORKSPACE;
+    return launch_combine(Xe, G, I, Xout, n, d, e, k, dtype, (uint32_t*)at(ws, 0), (int32_t*)at(ws, bm),
+                          (int32_t*)at(ws, bm + of), (hipStream_t)stream);
+}
+
+int ec_moe_forward(const void* X, const void* Wg, const void* W1, const void* W2, double c, void* Xout,
+                   float* S_out, float* G_out, int32_t* I_out, void* Xin_out, void* A_out, void* H_out,
+                   void* Xe_out, int64_t n, int64_t d, int64_t e, int64_t d_ff, int act, int dtype, void* ws,
+                   size_t ws_bytes, void* stream) {
+    int64_t k = 0;
+    if (ec_moe_capacity(n, e, c, &k) != EC_OK) return EC_ERR_INVALID_ARG;
+    const bool identity = (W1 == nullptr && W2 == nullptr);
+    if (!X || !Wg || !Xout || !sizes_ok(n, d, e, k) || !dtype_ok(dtype) || !act_ok(act) || !width_ok(d, dtype) ||
+        !all_aligned(X, Wg, W1, W2, Xout, S_out, G_out, I_out, Xin_out, A_out, H_out, Xe_out))
+        return EC_ERR_INVALID_ARG;
+    if (identity) {
+        if (act != EC_ACT_IDENTITY) return EC_ERR_INVALID_ARG;
+        d_ff = 0;
+    } else {
+        if (!W1 || !W2 || d_ff <= 0 || d_ff >= (int64_t)1 << 31 || !width_ok(d_ff, dtype))
+            return EC_ERR_INVALID_ARG;
+    }
+    const WsLayout L = ws_layout(n, d, e, k, d_ff, dtype, 0);
+    if (!ws_ok(ws, ws_bytes, L.total)) return EC_ERR_WORKSPACE;
+    hipStream_t st = (hipStream_t)stream;
+
+    float* St = (float*)at(ws, L.st);
+    float* G = G_out ? G_out : (float*)at(ws, L.g);
+    int32_t* I = I_out ? I_out : (int32_t*)at(ws, L.i);
+    void* Xin = Xin_out ? Xin_out : at(ws, L.xin);
+
+    int rc = launch_gate(X, Wg, S_out, St, n, d, e, dtype, dtype == EC_BF16 ? at(ws, L.wgt) : nullptr, st);
+    if (rc != EC_OK) return rc;
+    rc = launch_topk(St, n, e, k, G, I, (unsigned long long*)at(ws, L.sortkeys), st);
+    if (rc != EC_OK) return rc;
+    rc = launch_dispatch(X, I, Xin, n, d, e, k, dtype, st);
+    if (rc != EC_OK) return rc;
+    const void* Xe = Xin;  // identity experts
+    if (!identity) {
+        void* H = H_out ? H_out : at(ws, L.h);
+        void* Xe_w = Xe_out ? Xe_out : at(ws, L.xe);
+        rc = launch_ffn(Xin, W1, W2, Xe_w, A_out, H, e, k, d, d_ff, act, dtype, st);
+        if (rc != EC_OK) return rc;
+        Xe = Xe_w;
+    }
+    return launch_combine(Xe, G, I, Xout, n, d, e, k, dtype, (uint32_t*)at(ws, L.bitmap),
+                          (int32_t*)at(ws, L.offsets), (int32_t*)at(ws, L.inv), st);
+}
+
+int ec_moe_backward(const void* dY, const void* X, const void* Wg, const void* W1, const void* W2, const float* S,
+                    const float* G, const int32_t* I, const void* Xin, const void* A, const void* H,
+                    const void* Xe, void* dX, float* dWg, float* dW1, float* dW2, int64_t n, int64_t d, int64_t e,
+                    int64_t k, int64_t d_ff, int act, int dtype, void* ws, size_t ws_bytes, void* stream) {
+    if (!dY || !X || !Wg || !W1 || !W2 || !S || !G || !I || !Xin || !A || !H || !Xe || !dX || !dWg || !dW1 ||
+        !dW2 || !sizes_ok(n, d, e, k) || d_ff <= 0 || d_ff >= (int64_t)1 << 31 || !dtype_ok(dtype) ||
+        !act_ok(act) || !width_ok(d, dtype) || !width_ok(d_ff, dtype) ||
+        !all_aligned(dY, X, Wg, W1, W2, S, G, I, Xin, A, H, Xe, dX, dWg, dW1, dW2))
+        return EC_ERR_INVALID_ARG;
+    const WsLayout L = ws_layout(n, d, e, k, d_ff, dtype, 1);
+    if (!ws_ok(ws, ws_bytes, L.total)) return EC_ERR_WORKSPACE;
+    return launch_backward(dY, X, Wg, W1, W2, S, G, I, Xin, A, H, Xe, dX, dWg, dW1, dW2, n, d, e, k, d_ff, act,
+                           dtype, ws, L, (hipStream_t)stream);
+}
+
+int ec_moe_last_hip_error(void) { return g_last_hip_error; }
+
+const char* ec_moe_status_string(int status) {
+    switch (status) {
+        case EC_OK: return "EC_OK";
+        case EC_ERR_INVALID_ARG: return "EC_ERR_INVALID_ARG";
+        case EC_ERR_WORKSPACE: return "EC_ERR_WORKSPACE";
+        case EC_ERR_HIP: return "EC_ERR_HIP";
+        case EC_ERR_UNSUPPORTED: return "EC_ERR_UNSUPPORTED";
+        default: return "EC_UNKNOWN_STATUS";
+    }
+}
+
+const char* ec_moe_version(void) { return "0.1"; }
+
+}  // extern "C"

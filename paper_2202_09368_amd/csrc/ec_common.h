@@ -1,0 +1,120 @@
+// Internal helpers shared by the HIP translation units of libec_moe.so.
+// Nothing here is part of the public ABI (include/ec_moe.h).
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stddef.h>
+#include <stdint.h>
+
+#include "ec_moe.h"
+
+namespace ecmoe {
+
+typedef __bf16 bf16_t;
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef __bf16 bf16x4 __attribute__((ext_vector_type(4)));
+typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+typedef float floatx4 __attribute__((ext_vector_type(4)));
+typedef float floatx16 __attribute__((ext_vector_type(16)));
+
+constexpr int kWave = 64;  // CDNA wavefront width
+
+// Per-thread record of the last failing HIP call (read by ec_moe_last_hip_error).
+void set_last_hip_error(hipError_t err);
+
+// Returns EC_OK or records the error and returns EC_ERR_HIP.
+inline int check_launch() {
+    hipError_t err = hipGetLastError();
+    if (err != hipSuccess) {
+        set_last_hip_error(err);
+        return EC_ERR_HIP;
+    }
+    return EC_OK;
+}
+
+inline size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
+inline int64_t ceil_div(int64_t a, int64_t b) { return (a + b - 1) / b; }
+inline size_t elem_size(int dtype) { return dtype == EC_BF16 ? 2 : 4; }
+inline bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+
+// ---------------------------------------------------------------------------
+// Workspace layout.  One carve-up serves every entry point; regions that are
+// never live together in ec_moe_forward are still kept apart, the sizes are
+// small next to the activations.
+// ---------------------------------------------------------------------------
+struct WsLayout {
+    size_t wgt;        // bf16 [e_pad, d]: Wg transposed and padded (MFMA gate)
+    size_t st;         // float [e, n]: S^T
+    size_t g;          // float [e, k]
+    size_t i;          // int32 [e, k]
+    size_t xin;        // dtype [e, k, d]
+    size_t h;          // dtype [e, k, d_ff]
+    size_t xe;         // dtype [e, k, d]
+    size_t bitmap;     // uint32 [n, ceil(e/32)]: which experts chose a token
+    size_t offsets;    // int32 [n+1]: CSR row starts of the token-major index
+    size_t inv;        // int32 [e*k]: bucket rows (i*k+j) grouped by token, expert-ascending
+    size_t sortkeys;   // uint64 [e, pow2(k)]: top-k sort staging when a bucket exceeds LDS
+    size_t bwd;        // start of the backward-only region
+    size_t total;
+};
+
+WsLayout ws_layout(int64_t n, int64_t d, int64_t e, int64_t k, int64_t d_ff, int dtype, int with_backward);
+
+// Sizes of the backward-only region (defined with the backward kernels).
+size_t bwd_ws_bytes(int64_t n, int64_t d, int64_t e, int64_t k, int64_t d_ff, int dtype);
+
+// ---------------------------------------------------------------------------
+// Launchers (host side, arguments already validated by the ABI layer).
+// ---------------------------------------------------------------------------
+int launch_gate(const void* X, const void* Wg, float* S, float* St, int64_t n, int64_t d, int64_t e,
+                int dtype, void* wgt_ws, hipStream_t stream);
+int launch_topk(const float* St, int64_t n, int64_t e, int64_t k, float* G, int32_t* I,
+                unsigned long long* sortkeys_ws, hipStream_t stream);
+int launch_dispatch(const void* X, const int32_t* I, void* Xin, int64_t n, int64_t d, int64_t e, int64_t k,
+                    int dtype, hipStream_t stream);
+int launch_ffn(const void* Xin, const void* W1, const void* W2, void* Xe, void* A_save, void* H,
+               int64_t e, int64_t k, int64_t d, int64_t d_ff, int act, int dtype, hipStream_t stream);
+int launch_combine(const void* Xe, const float* G, const int32_t* I, void* Xout, int64_t n, int64_t d,
+                   int64_t e, int64_t k, int dtype, uint32_t* bitmap, int32_t* offsets, int32_t* inv,
+                   hipStream_t stream);
+int launch_backward(const void* dY, const void* X, const void* Wg, const void* W1, const void* W2,
+                    const float* S, const float* G, const int32_t* I, const void* Xin, const void* A,
+                    const void* H, const void* Xe, void* dX, float* dWg, float* dW1, float* dW2,
+                    int64_t n, int64_t d, int64_t e, int64_t k, int64_t d_ff, int act, int dtype,
+                    void* ws, const WsLayout& L, hipStream_t stream);
+
+// ---------------------------------------------------------------------------
+// Device helpers.
+// ---------------------------------------------------------------------------
+template <typename T> struct Cvt;
+template <> struct Cvt<float> {
+    static __device__ __forceinline__ float to_f32(float v) { return v; }
+    static __device__ __forceinline__ float from_f32(float v) { return v; }
+};
+template <> struct Cvt<bf16_t> {
+    static __device__ __forceinline__ float to_f32(bf16_t v) { return static_cast<float>(v); }
+    static __device__ __forceinline__ bf16_t from_f32(float v) { return static_cast<bf16_t>(v); }  // RNE
+};
+
+__device__ __forceinline__ float wave_reduce_max(float v) {
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) v = fmaxf(v, __shfl_xor(v, off, kWave));
+    return v;
+}
+__device__ __forceinline__ float wave_reduce_sum(float v) {
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) v += __shfl_xor(v, off, kWave);
+    return v;
+}
+
+// Exact-erf GeLU, a * Phi(a) (Hendrycks & Gimpel), evaluated in fp32.
+__device__ __forceinline__ float gelu_erf(float a) { return 0.5f * a * (1.0f + erff(a * 0.70710678118654752440f)); }
+
+template <int ACT>
+__device__ __forceinline__ float apply_act(float a) {
+    if (ACT == EC_ACT_RELU) return fmaxf(a, 0.0f);
+    if (ACT == EC_ACT_GELU) return gelu_erf(a);
+    return a;
+}
+
+}  // namespace ecmoe

@@ -1,0 +1,227 @@
+"""GPU parity: every C-ABI entry point against the CPU oracle on the same seeded inputs.
+
+Routing is discontinuous, so stages are compared one at a time: the scores S
+against the oracle's; TopK bit for bit with the oracle's TopK applied to the
+GPU's S ("same S"); dispatch bit for bit; FFN and combine against the oracle
+fed with the GPU's previous-stage output.
+"""
+import numpy as np
+import pytest
+import torch
+
+import workloads as wl
+from gpu_util import max_rel_err, out_tol, to_dev, to_f64, to_host, torch_dtype
+
+pytestmark = pytest.mark.gpu
+
+S_TOL = 1e-5
+
+
+@pytest.fixture(scope="module")
+def m():
+    if not torch.cuda.is_available():
+        pytest.skip("no GPU")
+    import paper_2202_09368_amd as mod
+    mod.lib()
+    return mod
+
+
+@pytest.fixture(scope="module")
+def ref():
+    from oracle import ec_moe_ref
+    return ec_moe_ref
+
+
+def _p(msg):
+    print(msg, flush=True)
+
+
+def _stagewise(m, ref, w, inp, check_ffn=True):
+    """Runs the layer stage by stage through the C ABI and checks each stage."""
+    n, d, e, k = w.n, w.d, w.e, w.k
+    dt = torch_dtype(w)
+    ws = m.alloc_workspace(n, d, e, k, w.d_ff, w.dtype)
+    X, Wg = to_dev(inp["X"]), to_dev(inp["Wg"])
+
+    _p(f"[{w.name}] gate n={n} d={d} e={e}")
+    S = torch.empty((n, e), dtype=torch.float32, device="cuda")
+    St = torch.empty((e, n), dtype=torch.float32, device="cuda")
+    m.ec_moe_gate(X, Wg, S, St, ws)
+    torch.cuda.synchronize()
+    S_h, St_h = to_host(S), to_host(St)
+    assert (St_h == S_h.T).all()
+    S_ref = ref.gate(inp["X"], inp["Wg"])
+    err = max_rel_err(S_h, S_ref)
+    _p(f"[{w.name}] S max rel err {err:.3e}")
+    assert err <= S_TOL
+    assert np.abs(S_h.astype(np.float64).sum(axis=1) - 1.0).max() < 1e-5 and (S_h >= 0).all()
+
+    _p(f"[{w.name}] topk k={k}")
+    G = torch.empty((e, k), dtype=torch.float32, device="cuda")
+    I = torch.empty((e, k), dtype=torch.int32, device="cuda")
+    m.ec_moe_topk_tokens(St, k, G, I, ws)
+    torch.cuda.synchronize()
+    G_h, I_h = to_host(G), to_host(I)
+    G_o, I_o = ref.topk_tokens(S_h, k)             # oracle TopK on the GPU's scores: must agree bit for bit
+    assert (I_h == I_o).all()
+    assert (G_h.view(np.uint32) == G_o.view(np.uint32)).all()
+    # selections made on the oracle's own S differ only where scores are within rounding of the threshold
+    _, I_os = ref.topk_tokens(S_ref, k)
+    diff = 0
+    for i in range(e):
+        flipped = np.array(sorted(set(I_os[i].tolist()) ^ set(I_h[i].tolist())), dtype=np.int64)
+        diff += len(flipped) // 2
+        if len(flipped):
+            thr = float(S_ref[I_os[i, -1], i])                    # the oracle's k-th score
+            assert (np.abs(S_ref[flipped, i].astype(np.float64) - thr) <= 2 * S_TOL * thr + 1e-30).all()
+    _p(f"[{w.name}] (expert, token) pairs differing from TopK(oracle S): {diff} of {e * k}")
+
+    _p(f"[{w.name}] dispatch")
+    Xin = torch.empty((e, k, d), dtype=dt, device="cuda")
+    m.ec_moe_dispatch(X, I, Xin)
+    torch.cuda.synchronize()
+    Xin_h = to_host(Xin)
+    assert (Xin_h == ref.dispatch(inp["X"], I_h)).all()
+
+    if w.d_ff > 0:
+        W1, W2 = to_dev(inp["W1"]), to_dev(inp["W2"])
+        _p(f"[{w.name}] expert_ffn d_ff={w.d_ff}")
+        Xe = torch.empty((e, k, d), dtype=dt, device="cuda")
+        m.ec_moe_expert_ffn(Xin, W1, W2, Xe, w.act, ws)
+        torch.cuda.synchronize()
+        Xe_h = to_host(Xe)
+        if check_ffn:
+            Xe_ref = ref.expert_ffn(Xin_h, inp["W1"], inp["W2"], w.act)
+            err = max_rel_err(Xe_h, Xe_ref)
+            _p(f"[{w.name}] X_e max rel err {err:.3e}")
+            assert err <= out_tol(w)
+    else:
+        Xe, Xe_h = Xin, Xin_h
+
+    _p(f"[{w.name}] combine")
+    Xout = torch.full((n, d), float("nan"), dtype=dt, device="cuda")
+    m.ec_moe_combine(Xe, G, I, Xout, ws)
+    torch.cuda.synchronize()
+    Xout_h = to_host(Xout)
+    Xout_ref = ref.combine(Xe_h, G_h, I_h, n)
+    err = max_rel_err(Xout_h, Xout_ref)
+    _p(f"[{w.name}] X_out (combine) max rel err {err:.3e}")
+    assert err <= (4e-3 if w.dtype == wl.DTYPE_BF16 else 1e-5)    # one bf16 rounding of an fp32 sum
+    counts = np.bincount(I_h.ravel(), minlength=n)
+    assert (to_f64(Xout_h)[counts == 0] == 0).all()                # unrouted tokens are written as zeros
+
+    _p(f"[{w.name}] forward")
+    Xout2 = torch.full((n, d), float("nan"), dtype=dt, device="cuda")
+    I2 = torch.empty_like(I)
+    G2 = torch.empty_like(G)
+    S2 = torch.empty_like(S)
+    W1d = to_dev(inp["W1"]) if w.d_ff > 0 else None
+    W2d = to_dev(inp["W2"]) if w.d_ff > 0 else None
+    m.ec_moe_forward(X, Wg, W1d, W2d, w.c, Xout2, w.act, ws, S_out=S2, G_out=G2, I_out=I2)
+    torch.cuda.synchronize()
+    assert (to_host(I2) == I_h).all() and (to_host(S2) == S_h).all()
+    assert (to_host(G2).view(np.uint32) == G_h.view(np.uint32)).all()
+    assert (to_host(Xout2) == Xout_h).all()                        # same kernels, same order: bit-identical
+    if w.d_ff > 0 and check_ffn:
+        # whole layer against the oracle's FFN + combine on the GPU's routing
+        full_ref = ref.combine(ref.expert_ffn(Xin_h, inp["W1"], inp["W2"], w.act), G_h, I_h, n)
+        err = max_rel_err(Xout_h, full_ref)
+        _p(f"[{w.name}] X_out (layer) max rel err {err:.3e}")
+        assert err <= out_tol(w)
+    return dict(S=S_h, I=I_h, G=G_h, Xout=Xout_h)
+
+
+# ----------------------------------------------------------- configurations --
+def test_cfg1_fp32_full(m, ref):
+    w = wl.WORKLOADS["cfg1"]
+    r = _stagewise(m, ref, w, wl.make_inputs(w))
+    # end to end against the oracle's own routing as well: at this size the selections coincide
+    f = ref.forward(*(wl.make_inputs(w)[key] for key in ("X", "Wg", "W1", "W2")), w.c, w.act)
+    if (f["I"] == r["I"]).all():
+        assert max_rel_err(r["Xout"], f["X_out"]) <= 1e-5
+
+
+@pytest.mark.parametrize("name,kw", [
+    ("cfg1", dict(n=300, d=60, e=5, c=2.0, d_ff=100)),          # fp32, nothing a multiple of a tile
+    ("cfg2", dict(n=1000, d=192, e=16, d_ff=328)),               # bf16, ragged M/N/K tails (k=125)
+    ("cfg2", dict(n=2048, d=256, e=8, d_ff=512, act=wl.ACT_RELU)),
+    ("cfg3", dict(n=4096, d=128, e=64, d_ff=256)),
+    ("cfg5", dict(n=8192, d=512, e=256)),                        # skewed routing-only, e=256
+    ("cfg5", dict(n=3000, d=264, e=40, c=1.0)),                  # d not a multiple of 64: generic gate
+])
+def test_reduced_shapes(m, ref, name, kw):
+    w = wl.scaled(wl.WORKLOADS[name], **kw)
+    _stagewise(m, ref, w, wl.make_inputs(w))
+
+
+def test_cfg2_full(m, ref):
+    w = wl.WORKLOADS["cfg2"]
+    _stagewise(m, ref, w, wl.make_inputs(w))
+
+
+# ------------------------------------------------------------------- top-k ---
+def _topk_case(m, ref, St_h, k):
+    e, n = St_h.shape
+    St = to_dev(St_h)
+    ws = m.alloc_workspace(n, 8, e, k, 0, wl.DTYPE_F32)
+    G = torch.empty((e, k), dtype=torch.float32, device="cuda")
+    I = torch.empty((e, k), dtype=torch.int32, device="cuda")
+    m.ec_moe_topk_tokens(St, k, G, I, ws)
+    torch.cuda.synchronize()
+    G_o, I_o = ref.topk_tokens(np.ascontiguousarray(St_h.T), k)
+    assert (to_host(I) == I_o).all()
+    assert (to_host(G).view(np.uint32) == G_o.view(np.uint32)).all()
+
+
+@pytest.mark.parametrize("n,e,k,kind", [
+    (1, 1, 1, "rand"), (7, 3, 7, "rand"), (1000, 4, 1, "rand"), (1024, 2, 1024, "rand"),
+    (5000, 3, 37, "rand"), (40000, 2, 300, "rand"), (70001, 3, 257, "rand"),
+    (20000, 2, 9000, "rand"),                       # bucket too large for LDS keys: workspace sort
+    (5000, 2, 5000, "rand"),                        # k = n
+    (9000, 3, 100, "const"),                        # every score equal: ties decided by token index
+    (9000, 3, 4000, "const"),
+    (30000, 2, 2000, "levels"),                     # few distinct values: exact ties across the k-th place
+    (70000, 2, 3000, "levels"),
+    (6000, 2, 64, "onehot"),                        # saturated softmax rows: exact 1.0 and 0.0
+    (50000, 2, 500, "tiny_range"),                  # all scores within a few ulps of each other
+])
+def test_topk_cases(m, ref, n, e, k, kind):
+    _p(f"[topk] n={n} e={e} k={k} {kind}")
+    r = np.random.default_rng(n + 31 * k)
+    if kind == "rand":
+        St = r.random((e, n), dtype=np.float32)
+    elif kind == "const":
+        St = np.full((e, n), 0.125, np.float32)
+    elif kind == "levels":
+        St = (np.floor(r.random((e, n)) * 5) / 5).astype(np.float32)
+    elif kind == "onehot":
+        St = (r.random((e, n)) < 0.3).astype(np.float32)
+    else:
+        base = np.float32(0.003)
+        St = (base.view(np.uint32) + r.integers(0, 4, (e, n)).astype(np.uint32)).view(np.float32)
+    _topk_case(m, ref, St, k)
+
+
+# ------------------------------------------------------------- determinism ---
+def test_forward_is_deterministic(m):
+    w = wl.scaled(wl.WORKLOADS["cfg2"], n=2048, d=256, e=16, d_ff=512)
+    inp = wl.make_inputs(w)
+    ws = m.alloc_workspace(w.n, w.d, w.e, w.k, w.d_ff, w.dtype)
+    t = {key: to_dev(inp[key]) for key in ("X", "Wg", "W1", "W2")}
+    outs = []
+    for _ in range(3):
+        Xout = torch.empty((w.n, w.d), dtype=torch.bfloat16, device="cuda")
+        m.ec_moe_forward(t["X"], t["Wg"], t["W1"], t["W2"], w.c, Xout, w.act, ws)
+        torch.cuda.synchronize()
+        outs.append(to_host(Xout))
+    assert (outs[0] == outs[1]).all() and (outs[0] == outs[2]).all()
+
+
+def test_zero_gate_all_ties(m, ref):
+    # Wg = 0: S = 1/e everywhere, every expert takes tokens 0..k-1 in order
+    w = wl.scaled(wl.WORKLOADS["cfg1"], n=512, d=32, e=4, d_ff=64)
+    inp = wl.make_inputs(w)
+    inp["Wg"] = np.zeros_like(inp["Wg"])
+    r = _stagewise(m, ref, w, inp)
+    assert (r["I"] == np.arange(w.k)[None, :]).all()
+    assert (r["S"] == np.float32(0.25)).all()
