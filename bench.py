@@ -1,0 +1,216 @@
+#!/usr/bin/env python3
+"""Benchmark of the expert-choice MoE layer forward on one MI355X.
+
+A step is one ec_moe_forward call (gate -> TopK over tokens -> dispatch ->
+expert FFN -> combine) on the "cfg2" workload: the paper's 0.1B/16E layer
+(Table 1: d=768, d_ff=3072, 16 experts) at capacity factor 2 over 8192 tokens,
+bf16 with fp32 accumulation, seeded synthetic Gaussian inputs already resident
+in HBM.  Prints ONE JSON line.
+
+Timed region 1 (the headline `value`): K back-to-back ec_moe_forward calls.
+Timed region 2 (for `roofline` and `stages`): the same K steps issued stage by
+stage through the C ABI with HIP events between the stages on the launch
+stream, so each kernel's own duration is measured live.
+The CPU oracle is timed on the host for the `cpu_baseline` leg.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+PEAK_HBM_GBS = 8000.0          # MI355X HBM3E, published
+PEAK_BF16_TFLOPS = 2500.0      # MI355X dense bf16 MFMA, published
+
+# HBM bytes per expert-FFN call (both products) from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE,
+# see profiles/; None until measured for the workload.
+MEASURED_FFN_TRAFFIC_BYTES = {}
+
+
+def parse_args():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=50)
+    ap.add_argument("--warmup", type=int, default=10)
+    ap.add_argument("--workload", default="cfg2", help="cfg2 (headline), cfg3, cfg5")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    return ap.parse_args()
+
+
+def main() -> int:
+    args = parse_args()
+    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
+        print("bench.py: this build measures the layer on ONE GPU only (no sharding, no collectives); "
+              "run with --gpus 1", file=sys.stderr)
+        return 2
+
+    import numpy as np
+    import torch
+
+    import paper_2202_09368_amd as m
+    import workloads as wl
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        return 2
+    m.lib()  # fails loudly when the HIP library is missing
+
+    w = wl.WORKLOADS[args.workload]
+    n, d, e, k, d_ff = w.n, w.d, w.e, w.k, w.d_ff
+    b = 2 if w.dtype == wl.DTYPE_BF16 else 4
+    inp = wl.make_inputs(w, with_dy=False)
+
+    def dev(a):
+        if a.dtype == np.uint16:
+            return torch.from_numpy(a.view(np.int16)).cuda().view(torch.bfloat16)
+        return torch.from_numpy(a).cuda()
+
+    X, Wg = dev(inp["X"]), dev(inp["Wg"])
+    W1 = dev(inp["W1"]) if d_ff else None
+    W2 = dev(inp["W2"]) if d_ff else None
+    dt = X.dtype
+    ws = m.alloc_workspace(n, d, e, k, d_ff, w.dtype)
+    Xout = torch.empty((n, d), dtype=dt, device="cuda")
+    K, W = args.steps, args.warmup
+
+    # ---- timed region 1: whole layer ----------------------------------------
+    for _ in range(W):
+        m.ec_moe_forward(X, Wg, W1, W2, w.c, Xout, w.act, ws)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(K):
+        m.ec_moe_forward(X, Wg, W1, W2, w.c, Xout, w.act, ws)
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    ms_per_step = (t1 - t0) * 1e3 / K
+    tokens_per_s = n / (ms_per_step * 1e-3)
+
+    # ---- timed region 2: stage by stage with HIP events ---------------------
+    St = torch.empty((e, n), dtype=torch.float32, device="cuda")
+    G = torch.empty((e, k), dtype=torch.float32, device="cuda")
+    I = torch.empty((e, k), dtype=torch.int32, device="cuda")
+    Xin = torch.empty((e, k, d), dtype=dt, device="cuda")
+    Xe = torch.empty((e, k, d), dtype=dt, device="cuda") if d_ff else Xin
+    names = ["gate", "topk", "dispatch"] + (["expert_ffn"] if d_ff else []) + ["combine"]
+
+    def staged_step(events):
+        events[0].record()
+        m.ec_moe_gate(X, Wg, None, St, ws)
+        events[1].record()
+        m.ec_moe_topk_tokens(St, k, G, I, ws)
+        events[2].record()
+        m.ec_moe_dispatch(X, I, Xin)
+        events[3].record()
+        j = 3
+        if d_ff:
+            m.ec_moe_expert_ffn(Xin, W1, W2, Xe, w.act, ws)
+            j += 1
+            events[j].record()
+        m.ec_moe_combine(Xe, G, I, Xout, ws)
+        events[j + 1].record()
+
+    # the FFN's hidden buffer and the combine index share the workspace start in the stage-wise
+    # calls; the stages run in order on one stream, so that is safe
+    ev = [[torch.cuda.Event(enable_timing=True) for _ in range(len(names) + 1)] for _ in range(K)]
+    warm = [torch.cuda.Event(enable_timing=True) for _ in range(len(names) + 1)]
+    for _ in range(max(W, 1)):
+        staged_step(warm)
+    torch.cuda.synchronize()
+    for s in range(K):
+        staged_step(ev[s])
+    torch.cuda.synchronize()
+    stage_us = {nm: sum(ev[s][j].elapsed_time(ev[s][j + 1]) for s in range(K)) * 1e3 / K
+                for j, nm in enumerate(names)}
+
+    alg_bytes = {
+        "gate": n * d * b + d * e * b + n * e * 4,
+        "topk": n * e * 4 + 8 * e * k,
+        "dispatch": 2 * e * k * d * b + 4 * e * k,
+        "combine": e * k * d * b + n * d * b + 8 * e * k,
+    }
+    stages = {}
+    for nm in names:
+        us = stage_us[nm]
+        entry = {"us": round(us, 2)}
+        if nm == "expert_ffn":
+            flops = 4.0 * e * k * d * d_ff
+            entry.update(flop=flops, tflops=round(flops / (us * 1e-6) / 1e12, 2),
+                         frac_of_mfma_peak=round(flops / (us * 1e-6) / 1e12 / PEAK_BF16_TFLOPS, 4))
+        else:
+            gbs = alg_bytes[nm] / (us * 1e-6) / 1e9
+            entry.update(bytes=alg_bytes[nm], gbs=round(gbs, 1), frac_of_hbm_peak=round(gbs / PEAK_HBM_GBS, 4))
+        stages[nm] = entry
+
+    if d_ff:
+        # dominant kernel: the grouped bf16 MFMA GEMM, launched twice per FFN call (X_in.W1, H.W2),
+        # 2*e*k*d*d_ff flop per launch
+        flop_per_launch = 2.0 * e * k * d * d_ff
+        avg_launch_s = stage_us["expert_ffn"] * 1e-6 / 2.0
+        achieved = flop_per_launch / avg_launch_s / 1e12
+        roofline = {"kernel": "gemm_bf16_kernel (grouped expert GEMM, 2 launches per FFN)", "bound": "mfma",
+                    "achieved": round(achieved, 2), "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
+                    "frac": round(achieved / PEAK_BF16_TFLOPS, 4),
+                    "avg_launch_us": round(avg_launch_s * 1e6, 2),
+                    "traffic": MEASURED_FFN_TRAFFIC_BYTES.get(w.name)}
+    else:
+        nm = max(("dispatch", "combine", "gate"), key=lambda s: stage_us[s])
+        gbs = alg_bytes[nm] / (stage_us[nm] * 1e-6) / 1e9
+        roofline = {"kernel": nm, "bound": "hbm", "achieved": round(gbs, 1), "peak": PEAK_HBM_GBS, "unit": "GB/s",
+                    "frac": round(gbs / PEAK_HBM_GBS, 4), "avg_launch_us": round(stage_us[nm], 2), "traffic": None}
+
+    # ---- CPU oracle on the host cores ---------------------------------------
+    cpu_baseline = None
+    if not args.no_cpu_baseline:
+        from oracle import ec_moe_ref as ref
+        try:
+            from threadpoolctl import threadpool_info
+            threads = max([p.get("num_threads", 1) for p in threadpool_info()] or [1])
+        except Exception:
+            threads = 1
+        threads = min(threads, os.cpu_count() or threads)
+        # bounded sample: all n tokens through gate/TopK/dispatch/combine, the FFN on the first
+        # `se` experts (experts cost the same), scaled to the full expert count
+        se = e if d_ff == 0 else max(1, min(e, int(8 * (1024 * 768 * 3072) / max(1, k * d * d_ff))))
+        t0 = time.perf_counter()
+        S_o = ref.gate(inp["X"], inp["Wg"])
+        G_o, I_o = ref.topk_tokens(S_o, k)
+        Xin_o = ref.dispatch(inp["X"], I_o)
+        t_route = time.perf_counter() - t0
+        t_ffn = 0.0
+        if d_ff:
+            t0 = time.perf_counter()
+            Xe_s = ref.expert_ffn(Xin_o[:se], inp["W1"][:se], inp["W2"][:se], w.act)
+            t_ffn = (time.perf_counter() - t0) * (e / se)
+            Xe_o = np.concatenate([Xe_s] * ((e + se - 1) // se))[:e] if se < e else Xe_s
+        else:
+            Xe_o = Xin_o
+        t0 = time.perf_counter()
+        ref.combine(Xe_o, G_o, I_o, n)
+        t_comb = time.perf_counter() - t0
+        total = t_route + t_ffn + t_comb
+        cpu_baseline = {"value": round(n / total, 1), "unit": "tokens/s", "cores": int(threads), "kind": "oracle",
+                        "sample": (f"one pass over all {n} tokens for gate/TopK/dispatch/combine; expert FFN on "
+                                   f"{se} of {e} experts scaled x{e / se:g}; float64 numpy"),
+                        "seconds": round(total, 2)}
+
+    out = {
+        "metric": "EC-MoE layer tokens/sec (1 GPU)", "value": round(tokens_per_s, 1), "unit": "tokens/s",
+        "n_gpus": 1, "steps": K, "warmup": W, "ms_per_step": round(ms_per_step, 4),
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "bf16" if w.dtype == wl.DTYPE_BF16 else "f32", "data": "synthetic",
+        "config": {"workload": f"{w.name}: EC-MoE layer forward, n={n} d={d} e={e} c={w.c:g} k={k} d_ff={d_ff}",
+                   "act": {0: "relu", 1: "gelu", 2: "identity"}[w.act], "seed": w.seed},
+        "roofline": roofline, "cpu_baseline": cpu_baseline, "stages": stages,
+    }
+    print(json.dumps(out), flush=True)
+    return 0
+
+
+if __name__ == "__main__":
+    sys.exit(main())
