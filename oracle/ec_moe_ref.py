@@ -19,8 +19,10 @@ Conventions (paper notation):
   X_e[e,k,d];  X_out[n,d].
 
 Readings where the paper is silent (each listed in the design notes too):
-  * TopK ties go to the lower token index; a bucket is ordered by descending
-    score, ties by ascending token index.
+  * TopK ties go to the lower token index (a token enters a bucket ahead of any
+    token with the same score and a higher index).  The paper does not say in
+    which order a bucket lists its k tokens ("the j-th selected token"); here a
+    bucket is listed by ascending token index.  X_out does not depend on it.
   * k = floor(n*c/e) evaluated in double.
   * Softmax is over the expert axis (one distribution per token).
   * G is the raw score (no renormalisation per token).
@@ -86,7 +88,8 @@ def topk_tokens(S: np.ndarray, k: int) -> Tuple[np.ndarray, np.ndarray]:
 
     S is float32 [n,e].  For expert i the tokens are ranked by descending
     S[:, i]; equal scores rank by ascending token index (stable sort), which
-    settles both who is admitted at the k-th place and the bucket order.
+    settles who is admitted at the k-th place.  The k admitted tokens are then
+    listed by ascending token index.
     """
     S = np.asarray(S)
     if S.dtype != np.float32:
@@ -99,8 +102,9 @@ def topk_tokens(S: np.ndarray, k: int) -> Tuple[np.ndarray, np.ndarray]:
     for i in range(e):
         col = S[:, i]
         order = np.argsort(-col, kind="stable")    # descending score, ties: low index first
-        I[i, :] = order[:k]
-        G[i, :] = col[order[:k]]
+        chosen = np.sort(order[:k])                # the bucket lists its tokens by ascending index
+        I[i, :] = chosen
+        G[i, :] = col[chosen]
     return G, I
 
 
