@@ -15,14 +15,12 @@ size_t topk_ws_bytes(int64_t n, int64_t e, int64_t k);  // topk.hip
 WsLayout ws_layout(int64_t n, int64_t d, int64_t e, int64_t k, int64_t d_ff, int dtype, int with_backward) {
     WsLayout L;
     const size_t es = elem_size(dtype);
-    const size_t e_pad = (size_t)ceil_div(e, 32) * 32;
     size_t off = 0;
     auto take = [&](size_t bytes) {
         size_t at = off;
         off = align_up(off + bytes, 256);
         return at;
     };
-    L.wgt = take(e_pad * (size_t)d * 2);
     L.st = take((size_t)e * n * 4);
     L.g = take((size_t)e * k * 4);
     L.i = take((size_t)e * k * 4);
@@ -32,6 +30,8 @@ WsLayout ws_layout(int64_t n, int64_t d, int64_t e, int64_t k, int64_t d_ff, int
     L.bitmap = take((size_t)n * (size_t)ceil_div(e, 32) * 4);
     L.offsets = take((size_t)(n + 1) * 4);
     L.inv = take((size_t)e * k * 4);
+    L.slot_cnt = take((size_t)n * 4);
+    L.slots = take((size_t)n * COMBINE_SLOT_CAP * 4);
     L.sortkeys = take(topk_ws_bytes(n, e, k));
     L.bwd = off;
     if (with_backward) take(bwd_ws_bytes(n, d, e, k, d_ff, dtype));
@@ -58,6 +58,18 @@ static bool ws_ok(const void* ws, size_t ws_bytes, size_t need) {
 }
 static unsigned char* at(void* ws, size_t off) { return static_cast<unsigned char*>(ws) + off; }
 
+CombineIndex combine_index_at(void* ws, const WsLayout& L, int64_t e) {
+    CombineIndex ix;
+    ix.use_slots = e <= COMBINE_SLOT_CAP;
+    ix.slot_cap = e <= 4 ? 4 : e <= 8 ? 8 : 16;
+    ix.slot_cnt = (int32_t*)at(ws, L.slot_cnt);
+    ix.slots = (int32_t*)at(ws, L.slots);
+    ix.bitmap = (uint32_t*)at(ws, L.bitmap);
+    ix.offsets = (int32_t*)at(ws, L.offsets);
+    ix.inv = (int32_t*)at(ws, L.inv);
+    return ix;
+}
+
 }  // namespace ecmoe
 
 using namespace ecmoe;
@@ -83,10 +95,8 @@ int ec_moe_gate(const void* X, const void* Wg, float* S, float* St, int64_t n, i
     if (!X || !Wg || (!S && !St) || n <= 0 || d <= 0 || e <= 0 || e > EC_MOE_MAX_EXPERTS || n >= (int64_t)1 << 31 ||
         !dtype_ok(dtype) || !all_aligned(X, Wg, S, St))
         return EC_ERR_INVALID_ARG;
-    // only the transposed, padded copy of Wg lives in the workspace
-    const size_t need = dtype == EC_BF16 ? align_up((size_t)ceil_div(e, 32) * 32 * (size_t)d * 2, 256) : 0;
-    if (!ws_ok(ws, ws_bytes, need)) return EC_ERR_WORKSPACE;
-    return launch_gate(X, Wg, S, St, n, d, e, dtype, need ? ws : nullptr, (hipStream_t)stream);
+    (void)ws; (void)ws_bytes;  // the gate needs no scratch
+    return launch_gate(X, Wg, S, St, n, d, e, dtype, nullptr, 0, (hipStream_t)stream);
 }
 
 int ec_moe_topk_tokens(const float* St, int64_t n, int64_t e, int64_t k, float* G, int32_t* I, void* ws,
@@ -94,7 +104,8 @@ int ec_moe_topk_tokens(const float* St, int64_t n, int64_t e, int64_t k, float* 
     if (!St || !G || !I || !sizes_ok(n, 1, e, k) || !all_aligned(St, G, I)) return EC_ERR_INVALID_ARG;
     const size_t need = topk_ws_bytes(n, e, k);
     if (!ws_ok(ws, ws_bytes, need)) return EC_ERR_WORKSPACE;
-    return launch_topk(St, n, e, k, G, I, need ? (unsigned long long*)ws : nullptr, (hipStream_t)stream);
+    return launch_topk(St, n, e, k, G, I, need ? (unsigned long long*)ws : nullptr, nullptr, nullptr, 0, nullptr,
+                       (hipStream_t)stream);
 }
 
 int ec_moe_dispatch(const void* X, const int32_t* I, void* Xin, int64_t n, int64_t d, int64_t e, int64_t k,
@@ -127,13 +138,20 @@ int ec_moe_combine(const void* Xe, const float* G, const int32_t* I, void* Xout,
     if (!Xe || !G || !I || !Xout || !sizes_ok(n, d, e, k) || !dtype_ok(dtype) || !width_ok(d, dtype) ||
         !all_aligned(Xe, G, I, Xout))
         return EC_ERR_INVALID_ARG;
-    // token-major index: bitmap, offsets, inverse list
-    const size_t bm = align_up((size_t)n * (size_t)ceil_div(e, 32) * 4, 256);
-    const size_t of = align_up((size_t)(n + 1) * 4, 256);
-    const size_t iv = align_up((size_t)e * k * 4, 256);
-    if (!ws_ok(ws, ws_bytes, bm + of + iv)) return EC_ERR_WORKSPACE;
-    return launch_combine(Xe, G, I, Xout, n, d, e, k, dtype, (uint32_t*)at(ws, 0), (int32_t*)at(ws, bm),
-                          (int32_t*)at(ws, bm + of), (hipStream_t)stream);
+    // token-major index: carved from the front of the workspace
+    WsLayout L;
+    size_t off = 0;
+    auto take = [&](size_t bytes) { size_t a = off; off = align_up(off + bytes, 256); return a; };
+    L.bitmap = take((size_t)n * (size_t)ceil_div(e, 32) * 4);
+    L.offsets = take((size_t)(n + 1) * 4);
+    L.inv = take((size_t)e * k * 4);
+    L.slot_cnt = take((size_t)n * 4);
+    L.slots = take((size_t)n * COMBINE_SLOT_CAP * 4);
+    if (!ws_ok(ws, ws_bytes, off)) return EC_ERR_WORKSPACE;
+    const CombineIndex ix = combine_index_at(ws, L, e);
+    int rc = launch_combine_index(I, n, e, k, ix, (hipStream_t)stream);
+    if (rc != EC_OK) return rc;
+    return launch_combine(Xe, G, I, Xout, n, d, e, k, dtype, ix, (hipStream_t)stream);
 }
 
 int ec_moe_forward(const void* X, const void* Wg, const void* W1, const void* W2, double c, void* Xout,
@@ -162,9 +180,11 @@ int ec_moe_forward(const void* X, const void* Wg, const void* W1, const void* W2
     int32_t* I = I_out ? I_out : (int32_t*)at(ws, L.i);
     void* Xin = Xin_out ? Xin_out : at(ws, L.xin);
 
-    int rc = launch_gate(X, Wg, S_out, St, n, d, e, dtype, dtype == EC_BF16 ? at(ws, L.wgt) : nullptr, st);
+    const CombineIndex ix = combine_index_at(ws, L, e);
+    int rc = launch_gate(X, Wg, S_out, St, n, d, e, dtype, combine_zero_ptr(ix), combine_zero_words(ix, n, e), st);
     if (rc != EC_OK) return rc;
-    rc = launch_topk(St, n, e, k, G, I, (unsigned long long*)at(ws, L.sortkeys), st);
+    rc = launch_topk(St, n, e, k, G, I, (unsigned long long*)at(ws, L.sortkeys), ix.use_slots ? ix.slot_cnt : nullptr,
+                     ix.slots, ix.slot_cap, ix.use_slots ? nullptr : ix.bitmap, st);
     if (rc != EC_OK) return rc;
     rc = launch_dispatch(X, I, Xin, n, d, e, k, dtype, st);
     if (rc != EC_OK) return rc;
@@ -176,8 +196,7 @@ int ec_moe_forward(const void* X, const void* Wg, const void* W1, const void* W2
         if (rc != EC_OK) return rc;
         Xe = Xe_w;
     }
-    return launch_combine(Xe, G, I, Xout, n, d, e, k, dtype, (uint32_t*)at(ws, L.bitmap),
-                          (int32_t*)at(ws, L.offsets), (int32_t*)at(ws, L.inv), st);
+    return launch_combine(Xe, G, I, Xout, n, d, e, k, dtype, ix, st);
 }
 
 int ec_moe_backward(const void* dY, const void* X, const void* Wg, const void* W1, const void* W2, const float* S,

@@ -2,12 +2,8 @@
 //
 // dispatch: X_in[i,j,:] = X[I[i,j],:] -- a row gather with 16-byte lanes.
 // combine:  X_out[l,:] = sum_{(i,j): I[i,j]=l} G[i,j] X_e[i,j,:], deterministic.
-//   A token-major index is built from I without sorting and without float atomics:
-//     a) bitmap[l] |= 1 << i          (integer OR commutes: order-free)
-//     b) offsets = exclusive scan of popcount(bitmap[l])
-//     c) inv[offsets[l] + popcount(bitmap[l] & bits below i)] = i*k + j
-//   so each token's list is already in ascending expert order, and
-//     d) one group of lanes per token adds its rows in that order in fp32.
+//   A token-major index is built from I with integer atomics only (see below); one group of
+//   lanes per token then adds that token's bucket rows in ascending expert order in fp32.
 #include "ec_common.h"
 
 namespace ecmoe {
@@ -67,6 +63,13 @@ int launch_dispatch(const void* X, const int32_t* I, void* Xin, int64_t n, int64
 }
 
 // ------------------------------------------------------------------- combine
+// Token-major index of the routing, two forms:
+//  * slot lists (e <= COMBINE_SLOT_CAP): slot_cnt[l] experts chose token l and left their bucket rows
+//    in slots[l*cap ...] in arrival order; the combine kernel visits them in ascending row order,
+//    which is ascending expert order because an expert holds a token at most once.
+//  * CSR (any e): bitmap[l] has one bit per expert, offsets = exclusive scan of its popcounts,
+//    inv[offsets[l] + (number of set bits below i)] = i*k + j -- already expert-ascending.
+// Both are built with integer atomics only (OR / counting), so the result never depends on timing.
 __global__ void __launch_bounds__(256)
 fill_u32_kernel(uint32_t* __restrict__ p, long long count, uint32_t v) {
     for (long long i = (long long)blockIdx.x * 256 + threadIdx.x; i < count; i += (long long)gridDim.x * 256) p[i] = v;
@@ -80,38 +83,72 @@ bitmap_kernel(const int32_t* __restrict__ I, uint32_t* __restrict__ bitmap, long
     }
 }
 
-// Exclusive scan of per-token expert counts.  One 1024-thread workgroup; tokens
-// are taken in consecutive chunks of 1024 so loads stay coalesced.
+__global__ void __launch_bounds__(256)
+slots_kernel(const int32_t* __restrict__ I, int32_t* __restrict__ slot_cnt, int32_t* __restrict__ slots,
+             long long rows, int cap) {
+    for (long long r = (long long)blockIdx.x * 256 + threadIdx.x; r < rows; r += (long long)gridDim.x * 256) {
+        const int l = I[r];
+        const int s = atomicAdd(&slot_cnt[l], 1);
+        if (s < cap) slots[(size_t)l * cap + s] = (int32_t)r;
+    }
+}
+
+// Exclusive scan of per-token expert counts by one 1024-thread workgroup.  Each round takes
+// SCAN_PER_THREAD * 1024 tokens: token = round base + u*1024 + tid, so loads stay coalesced.
+constexpr int SCAN_PER_THREAD = 8;
 __global__ void __launch_bounds__(1024)
 offsets_kernel(const uint32_t* __restrict__ bitmap, int32_t* __restrict__ offsets, int n, int words) {
-    __shared__ unsigned int wave_tot[16];
-    __shared__ unsigned int carry;
+    __shared__ unsigned int wave_tot[SCAN_PER_THREAD][16];
+    __shared__ unsigned int wave_base[SCAN_PER_THREAD][16];
+    __shared__ unsigned int carry_s;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    if (tid == 0) carry = 0;
-    __syncthreads();
-    for (int l0 = 0; l0 < n; l0 += 1024) {
-        int l = l0 + tid;
-        unsigned int c = 0;
-        if (l < n)
-            for (int w = 0; w < words; ++w) c += __popc(bitmap[(size_t)l * words + w]);
-        unsigned int incl = c;
+    unsigned int carry = 0;
+    for (int base = 0; base < n; base += SCAN_PER_THREAD * 1024) {
+        unsigned int c[SCAN_PER_THREAD], incl[SCAN_PER_THREAD];
+#pragma unroll
+        for (int u = 0; u < SCAN_PER_THREAD; ++u) {
+            const int l = base + u * 1024 + tid;
+            unsigned int v = 0;
+            if (l < n)
+                for (int w = 0; w < words; ++w) v += __popc(bitmap[(size_t)l * words + w]);
+            c[u] = v;
+            incl[u] = v;
+        }
 #pragma unroll
         for (int off = 1; off < 64; off <<= 1) {
-            unsigned int o = __shfl_up(incl, off, kWave);
-            if (lane >= off) incl += o;
-        }
-        if (lane == 63) wave_tot[wave] = incl;
-        __syncthreads();
-        unsigned int before = carry, total = 0;
 #pragma unroll
-        for (int w = 0; w < 16; ++w) {
-            unsigned int t = wave_tot[w];
-            before += w < wave ? t : 0u;
-            total += t;
+            for (int u = 0; u < SCAN_PER_THREAD; ++u) {
+                unsigned int o = __shfl_up(incl[u], off, kWave);
+                if (lane >= off) incl[u] += o;
+            }
         }
-        if (l < n) offsets[l] = (int32_t)(before + incl - c);
+        if (lane == 63) {
+#pragma unroll
+            for (int u = 0; u < SCAN_PER_THREAD; ++u) wave_tot[u][wave] = incl[u];
+        }
         __syncthreads();
-        if (tid == 0) carry += total;
+        if (wave == 0) {
+            // 128 wavefront totals in (u, wave) order: two per lane, exclusive scan across the wavefront
+            const int a = 2 * lane, b = 2 * lane + 1;
+            unsigned int ta = wave_tot[a >> 4][a & 15], tb = wave_tot[b >> 4][b & 15];
+            unsigned int pair = ta + tb, in2 = pair;
+#pragma unroll
+            for (int off = 1; off < 64; off <<= 1) {
+                unsigned int o = __shfl_up(in2, off, kWave);
+                if (lane >= off) in2 += o;
+            }
+            const unsigned int ex = in2 - pair;
+            wave_base[a >> 4][a & 15] = ex;
+            wave_base[b >> 4][b & 15] = ex + ta;
+            if (lane == 63) carry_s = in2;
+        }
+        __syncthreads();
+#pragma unroll
+        for (int u = 0; u < SCAN_PER_THREAD; ++u) {
+            const int l = base + u * 1024 + tid;
+            if (l < n) offsets[l] = (int32_t)(carry + wave_base[u][wave] + incl[u] - c[u]);
+        }
+        carry += carry_s;
         __syncthreads();
     }
     if (tid == 0) offsets[n] = (int32_t)carry;
@@ -132,24 +169,47 @@ inverse_index_kernel(const int32_t* __restrict__ I, const uint32_t* __restrict__
     }
 }
 
-// One token per group of `tpr` threads; each thread owns 16 bytes of the row
-// (8 bf16 / 4 fp32) per step and accumulates in fp32.
-template <typename T, int VEC>
+// One token per group of `tpr` threads; each thread owns 16 bytes of the row (8 bf16 / 4 fp32) per
+// step and accumulates in fp32.  CAP = 0: rows come from the CSR lists (expert-ascending).
+// CAP > 0: rows come from the token's slot list (capacity CAP), visited in ascending row order
+// by repeated minimum -- the lists are short, the capacity factor on average.
+template <typename T, int VEC, int CAP>
 __global__ void __launch_bounds__(256)
 combine_kernel(const T* __restrict__ Xe, const float* __restrict__ G, const int32_t* __restrict__ offsets,
                const int32_t* __restrict__ inv, T* __restrict__ Xout, int n, int d, int tpr) {
     typedef T vec_t __attribute__((ext_vector_type(VEC)));
+    constexpr int NRAW = CAP > 0 ? CAP : 1;
     const int tok_per_block = 256 / tpr;
     const int sub = threadIdx.x / tpr, t = threadIdx.x % tpr;
     const int vec_per_row = d / VEC;
     for (int l = blockIdx.x * tok_per_block + sub; l < n; l += gridDim.x * tok_per_block) {
-        const int beg = offsets[l], end = offsets[l + 1];
+        int raw[NRAW];
+        int cnt, beg = 0;
+        if (CAP > 0) {
+            cnt = offsets[l];  // experts that chose this token
+            cnt = cnt < CAP ? cnt : CAP;
+#pragma unroll
+            for (int q = 0; q < NRAW; ++q) raw[q] = q < cnt ? inv[(size_t)l * CAP + q] : 0x7FFFFFFF;
+        } else {
+            beg = offsets[l];
+            cnt = offsets[l + 1] - beg;
+        }
         for (int v = t; v < vec_per_row; v += tpr) {
             float acc[VEC];
 #pragma unroll
             for (int q = 0; q < VEC; ++q) acc[q] = 0.0f;
-            for (int p = beg; p < end; ++p) {
-                const int r = inv[p];
+            int last = -1;
+            for (int p = 0; p < cnt; ++p) {
+                int r;
+                if (CAP > 0) {
+                    int best = 0x7FFFFFFF;
+#pragma unroll
+                    for (int q = 0; q < NRAW; ++q) best = (raw[q] > last && raw[q] < best) ? raw[q] : best;
+                    r = best;
+                    last = best;
+                } else {
+                    r = inv[beg + p];
+                }
                 const float g = G[r];
                 vec_t x = *reinterpret_cast<const vec_t*>(Xe + (size_t)r * d + (size_t)v * VEC);
 #pragma unroll
@@ -163,45 +223,70 @@ combine_kernel(const T* __restrict__ Xe, const float* __restrict__ G, const int3
     }
 }
 
-int launch_combine(const void* Xe, const float* G, const int32_t* I, void* Xout, int64_t n, int64_t d,
-                   int64_t e, int64_t k, int dtype, uint32_t* bitmap, int32_t* offsets, int32_t* inv,
-                   hipStream_t stream) {
-    const long long rows = (long long)e * k;
-    const int words = (int)ceil_div(e, 32);
-    const long long bm_words = (long long)n * words;
-    auto blocks_for = [](long long items) {
-        long long b = (items + 255) / 256;
-        return (unsigned)(b > 16384 ? 16384 : (b < 1 ? 1 : b));
-    };
-    hipLaunchKernelGGL(fill_u32_kernel, dim3(blocks_for(bm_words)), dim3(256), 0, stream, bitmap, bm_words, 0u);
-    hipLaunchKernelGGL(bitmap_kernel, dim3(blocks_for(rows)), dim3(256), 0, stream, I, bitmap, rows, (int)k, words);
-    hipLaunchKernelGGL(offsets_kernel, dim3(1), dim3(1024), 0, stream, bitmap, offsets, (int)n, words);
-    hipLaunchKernelGGL(inverse_index_kernel, dim3(blocks_for(rows)), dim3(256), 0, stream, I, bitmap, offsets, inv,
-                       rows, (int)k, words);
-    int rc = check_launch();
-    if (rc != EC_OK) return rc;
+static unsigned blocks_for(long long items) {
+    long long b = (items + 255) / 256;
+    return (unsigned)(b > 16384 ? 16384 : (b < 1 ? 1 : b));
+}
 
-    if (dtype == EC_BF16) {
-        int vec = (int)(d / 8);
-        int tpr = pick_threads_per_row(vec);
-        long long blocks = ceil_div(n, 256 / tpr);
-        if (blocks > (1 << 20)) blocks = 1 << 20;
-        hipLaunchKernelGGL((combine_kernel<bf16_t, 8>), dim3((unsigned)blocks), dim3(256), 0, stream,
-                           (const bf16_t*)Xe, G, offsets, inv, (bf16_t*)Xout, (int)n, (int)d, tpr);
-    } else if (d % 4 == 0) {
-        int vec = (int)(d / 4);
-        int tpr = pick_threads_per_row(vec);
-        long long blocks = ceil_div(n, 256 / tpr);
-        if (blocks > (1 << 20)) blocks = 1 << 20;
-        hipLaunchKernelGGL((combine_kernel<float, 4>), dim3((unsigned)blocks), dim3(256), 0, stream,
-                           (const float*)Xe, G, offsets, inv, (float*)Xout, (int)n, (int)d, tpr);
+// Builds the token-major index from I alone (stand-alone combine; the forward pass gets it
+// from the gate and top-k kernels instead).
+int launch_combine_index(const int32_t* I, int64_t n, int64_t e, int64_t k, const CombineIndex& ix,
+                         hipStream_t stream) {
+    const long long rows = (long long)e * k;
+    if (ix.use_slots) {
+        hipLaunchKernelGGL(fill_u32_kernel, dim3(blocks_for(n)), dim3(256), 0, stream, (uint32_t*)ix.slot_cnt,
+                           (long long)n, 0u);
+        hipLaunchKernelGGL(slots_kernel, dim3(blocks_for(rows)), dim3(256), 0, stream, I, ix.slot_cnt, ix.slots, rows,
+                           ix.slot_cap);
     } else {
-        int tpr = pick_threads_per_row(d);
-        long long blocks = ceil_div(n, 256 / tpr);
-        if (blocks > (1 << 20)) blocks = 1 << 20;
-        hipLaunchKernelGGL((combine_kernel<float, 1>), dim3((unsigned)blocks), dim3(256), 0, stream,
-                           (const float*)Xe, G, offsets, inv, (float*)Xout, (int)n, (int)d, tpr);
+        const int words = (int)ceil_div(e, 32);
+        hipLaunchKernelGGL(fill_u32_kernel, dim3(blocks_for((long long)n * words)), dim3(256), 0, stream, ix.bitmap,
+                           (long long)n * words, 0u);
+        hipLaunchKernelGGL(bitmap_kernel, dim3(blocks_for(rows)), dim3(256), 0, stream, I, ix.bitmap, rows, (int)k,
+                           words);
     }
+    return check_launch();
+}
+
+// Applies Eq. 4 given a filled index (slot lists, or the bitmap from which the CSR lists are finished here).
+int launch_combine(const void* Xe, const float* G, const int32_t* I, void* Xout, int64_t n, int64_t d,
+                   int64_t e, int64_t k, int dtype, const CombineIndex& ix, hipStream_t stream) {
+    const long long rows = (long long)e * k;
+    const int32_t* offs = ix.slot_cnt;
+    const int32_t* list = ix.slots;
+    if (!ix.use_slots) {
+        const int words = (int)ceil_div(e, 32);
+        hipLaunchKernelGGL(offsets_kernel, dim3(1), dim3(1024), 0, stream, ix.bitmap, ix.offsets, (int)n, words);
+        hipLaunchKernelGGL(inverse_index_kernel, dim3(blocks_for(rows)), dim3(256), 0, stream, I, ix.bitmap, ix.offsets,
+                           ix.inv, rows, (int)k, words);
+        int rc = check_launch();
+        if (rc != EC_OK) return rc;
+        offs = ix.offsets;
+        list = ix.inv;
+    }
+#define EC_COMBINE_LAUNCH(TYPE, VECV, NVEC)                                                                   \
+    do {                                                                                                      \
+        int tpr = pick_threads_per_row(NVEC);                                                                 \
+        long long blocks = ceil_div(n, 256 / tpr);                                                            \
+        if (blocks > (1 << 20)) blocks = 1 << 20;                                                             \
+        dim3 grid((unsigned)blocks), block(256);                                                              \
+        if (!ix.use_slots)                                                                                    \
+            hipLaunchKernelGGL((combine_kernel<TYPE, VECV, 0>), grid, block, 0, stream, (const TYPE*)Xe, G,   \
+                               offs, list, (TYPE*)Xout, (int)n, (int)d, tpr);                                 \
+        else if (ix.slot_cap == 4)                                                                            \
+            hipLaunchKernelGGL((combine_kernel<TYPE, VECV, 4>), grid, block, 0, stream, (const TYPE*)Xe, G,   \
+                               offs, list, (TYPE*)Xout, (int)n, (int)d, tpr);                                 \
+        else if (ix.slot_cap == 8)                                                                            \
+            hipLaunchKernelGGL((combine_kernel<TYPE, VECV, 8>), grid, block, 0, stream, (const TYPE*)Xe, G,   \
+                               offs, list, (TYPE*)Xout, (int)n, (int)d, tpr);                                 \
+        else                                                                                                  \
+            hipLaunchKernelGGL((combine_kernel<TYPE, VECV, 16>), grid, block, 0, stream, (const TYPE*)Xe, G,  \
+                               offs, list, (TYPE*)Xout, (int)n, (int)d, tpr);                                 \
+    } while (0)
+    if (dtype == EC_BF16) EC_COMBINE_LAUNCH(bf16_t, 8, d / 8);
+    else if (d % 4 == 0) EC_COMBINE_LAUNCH(float, 4, d / 4);
+    else EC_COMBINE_LAUNCH(float, 1, d);
+#undef EC_COMBINE_LAUNCH
     return check_launch();
 }
 

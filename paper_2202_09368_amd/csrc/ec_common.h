@@ -43,16 +43,17 @@ inline bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 
 // small next to the activations.
 // ---------------------------------------------------------------------------
 struct WsLayout {
-    size_t wgt;        // bf16 [e_pad, d]: Wg transposed and padded (MFMA gate)
     size_t st;         // float [e, n]: S^T
     size_t g;          // float [e, k]
     size_t i;          // int32 [e, k]
     size_t xin;        // dtype [e, k, d]
     size_t h;          // dtype [e, k, d_ff]
     size_t xe;         // dtype [e, k, d]
-    size_t bitmap;     // uint32 [n, ceil(e/32)]: which experts chose a token
+    size_t bitmap;     // uint32 [n, ceil(e/32)]: which experts chose a token      (CSR form, e > COMBINE_SLOT_CAP)
     size_t offsets;    // int32 [n+1]: CSR row starts of the token-major index
     size_t inv;        // int32 [e*k]: bucket rows (i*k+j) grouped by token, expert-ascending
+    size_t slot_cnt;   // int32 [n]: experts that chose a token                     (slot form, e <= COMBINE_SLOT_CAP)
+    size_t slots;      // int32 [n, COMBINE_SLOT_CAP]: their bucket rows, arrival order
     size_t sortkeys;   // uint64 [e, pow2(k)]: top-k sort staging when a bucket exceeds LDS
     size_t bwd;        // start of the backward-only region
     size_t total;
@@ -63,20 +64,40 @@ WsLayout ws_layout(int64_t n, int64_t d, int64_t e, int64_t k, int64_t d_ff, int
 // Sizes of the backward-only region (defined with the backward kernels).
 size_t bwd_ws_bytes(int64_t n, int64_t d, int64_t e, int64_t k, int64_t d_ff, int dtype);
 
+// Token-major index of the routing handed from the top-k stage to the combine stage.
+constexpr int COMBINE_SLOT_CAP = 16;
+struct CombineIndex {
+    bool use_slots;      // e <= COMBINE_SLOT_CAP: per-token slot lists; otherwise bitmap + CSR
+    int32_t* slot_cnt;   // [n]
+    int32_t* slots;      // [n, slot_cap]
+    int slot_cap;
+    uint32_t* bitmap;    // [n, ceil(e/32)]
+    int32_t* offsets;    // [n+1]
+    int32_t* inv;        // [e*k]
+};
+CombineIndex combine_index_at(void* ws_base, const WsLayout& L, int64_t e);
+// 32-bit words that must be zero before the index is filled, and where they start.
+inline uint32_t* combine_zero_ptr(const CombineIndex& ix) { return ix.use_slots ? (uint32_t*)ix.slot_cnt : ix.bitmap; }
+inline int64_t combine_zero_words(const CombineIndex& ix, int64_t n, int64_t e) {
+    return ix.use_slots ? n : n * ceil_div(e, 32);
+}
+
 // ---------------------------------------------------------------------------
 // Launchers (host side, arguments already validated by the ABI layer).
 // ---------------------------------------------------------------------------
 int launch_gate(const void* X, const void* Wg, float* S, float* St, int64_t n, int64_t d, int64_t e,
-                int dtype, void* wgt_ws, hipStream_t stream);
+                int dtype, uint32_t* zero_buf, int64_t zero_words, hipStream_t stream);
 int launch_topk(const float* St, int64_t n, int64_t e, int64_t k, float* G, int32_t* I,
-                unsigned long long* sortkeys_ws, hipStream_t stream);
+                unsigned long long* sortkeys_ws, int32_t* slot_cnt, int32_t* slots, int slot_cap, uint32_t* bitmap,
+                hipStream_t stream);
+int launch_combine_index(const int32_t* I, int64_t n, int64_t e, int64_t k, const CombineIndex& ix,
+                         hipStream_t stream);
 int launch_dispatch(const void* X, const int32_t* I, void* Xin, int64_t n, int64_t d, int64_t e, int64_t k,
                     int dtype, hipStream_t stream);
 int launch_ffn(const void* Xin, const void* W1, const void* W2, void* Xe, void* A_save, void* H,
                int64_t e, int64_t k, int64_t d, int64_t d_ff, int act, int dtype, hipStream_t stream);
 int launch_combine(const void* Xe, const float* G, const int32_t* I, void* Xout, int64_t n, int64_t d,
-                   int64_t e, int64_t k, int dtype, uint32_t* bitmap, int32_t* offsets, int32_t* inv,
-                   hipStream_t stream);
+                   int64_t e, int64_t k, int dtype, const CombineIndex& ix, hipStream_t stream);
 int launch_backward(const void* dY, const void* X, const void* Wg, const void* W1, const void* W2,
                     const float* S, const float* G, const int32_t* I, const void* Xin, const void* A,
                     const void* H, const void* Xe, void* dX, float* dWg, float* dW1, float* dW2,

@@ -1,7 +1,7 @@
 // Gating scores S = Softmax(X.Wg) over the expert axis (Sec. 3.2, Eq. 2; Sec. 3.4).
 //
 // Two kernels:
-//  * gate_mfma_kernel   bf16 inputs, d % 64 == 0, e <= 256.  Computes Z^T = Wg^T.X^T
+//  * gate_mfma_kernel   bf16 inputs, d % 64 == 0, e % 8 == 0, e <= 256.  Computes Z^T = Wg^T.X^T
 //    on the matrix cores with experts as the MFMA row axis and tokens as the
 //    column axis, so that one token's logits sit in the registers of two lanes
 //    (lane and lane^32) and the softmax needs a single cross-lane exchange.
@@ -12,43 +12,34 @@
 namespace ecmoe {
 
 // ---------------------------------------------------------------------------
-// Wg [d,e] -> Wgt [e_pad, d] bf16 (rows >= e are zero).  Tiny; runs once per call.
+// MFMA gate.  Block = NW wavefronts, 32 tokens per wavefront.  ET = number of
+// 32-expert tiles held per wavefront (e_pad = 32*ET).  A stage of 64 rows of Wg
+// sits in LDS in the matrix's own row-major [k][expert] form; transposing LDS
+// reads (ds_read_b64_tr_b16) hand each lane the 2 x 4 consecutive-k values of
+// its expert, so Wg needs no transposed copy.  The block also clears
+// `zero_words` 32-bit words at `zero_buf` (counters the later stages use).
 // ---------------------------------------------------------------------------
-__global__ void wg_transpose_kernel(const bf16_t* __restrict__ Wg, bf16_t* __restrict__ Wgt,
-                                    int d, int e, int e_pad) {
-    __shared__ bf16_t tile[32][33];
-    const int t0 = blockIdx.x * 32;  // d index
-    const int i0 = blockIdx.y * 32;  // expert index
-    const int tx = threadIdx.x & 31, ty = threadIdx.x >> 5;  // 32 x 8
-    for (int r = ty; r < 32; r += 8) {
-        int t = t0 + r, i = i0 + tx;
-        tile[r][tx] = (t < d && i < e) ? Wg[(size_t)t * e + i] : static_cast<bf16_t>(0.0f);
-    }
-    __syncthreads();
-    for (int r = ty; r < 32; r += 8) {
-        int i = i0 + r, t = t0 + tx;
-        if (i < e_pad && t < d) Wgt[(size_t)i * d + t] = tile[tx][r];
-    }
-}
+constexpr int GATE_BK = 64;  // contraction elements per LDS stage
 
-// ---------------------------------------------------------------------------
-// MFMA gate.  Block = 256 threads = 4 wavefronts, 32 tokens per wavefront.
-// ET = number of 32-expert tiles held per wavefront (e_pad = 32*ET).
-// ---------------------------------------------------------------------------
-constexpr int GATE_BK = 64;       // contraction elements per LDS stage
-constexpr int GATE_LDS_STRIDE = GATE_BK + 8;  // bf16 elements; 144-byte rows keep 16-byte reads conflict-free
-
-template <int ET>
-__global__ void __launch_bounds__(256)
-gate_mfma_kernel(const bf16_t* __restrict__ X, const bf16_t* __restrict__ Wgt,
-                 float* __restrict__ S, float* __restrict__ St, int n, int d, int e) {
+template <int ET, int NW>
+__global__ void __launch_bounds__(64 * NW)
+gate_mfma_kernel(const bf16_t* __restrict__ X, const bf16_t* __restrict__ Wg, float* __restrict__ S,
+                 float* __restrict__ St, int n, int d, int e, uint32_t* __restrict__ zero_buf, int zero_words) {
     constexpr int E_PAD = 32 * ET;
-    __shared__ __attribute__((aligned(16))) bf16_t Wt[E_PAD * GATE_LDS_STRIDE];
+    constexpr int NT = 64 * NW;
+    constexpr int PITCH = ET == 1 ? 32 : E_PAD + 32;  // four consecutive rows fall in four distinct 64-byte bank groups
+    constexpr int CHUNKS = GATE_BK * (E_PAD / 8);     // 16-byte chunks per stage
+    constexpr int CPT = (CHUNKS + NT - 1) / NT;       // chunks per thread
+    __shared__ __attribute__((aligned(16))) bf16_t Wk[GATE_BK * PITCH];
+    typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
+    typedef __attribute__((address_space(3))) bf16x4 lds_bf16x4;
 
     const int tid = threadIdx.x;
+    for (int i = blockIdx.x * NT + tid; i < zero_words; i += gridDim.x * NT) zero_buf[i] = 0u;
+
     const int lane = tid & 63, wave = tid >> 6;
-    const int col = lane & 31, half = lane >> 5;
-    const int tok = blockIdx.x * 128 + wave * 32 + col;
+    const int col = lane & 31, half = lane >> 5, l16 = lane & 15;
+    const int tok = blockIdx.x * (32 * NW) + wave * 32 + col;
     const int tok_ld = tok < n ? tok : n - 1;  // clamp loads, predicate stores
     const bf16_t* xrow = X + (size_t)tok_ld * d + half * 32;
 
@@ -58,43 +49,48 @@ gate_mfma_kernel(const bf16_t* __restrict__ X, const bf16_t* __restrict__ Wgt,
 #pragma unroll
         for (int r = 0; r < 16; ++r) acc[te][r] = 0.0f;
 
-    bf16x8 wreg[ET];
+    u32x4 wreg[CPT];
     bf16x8 xreg[4];
     auto load_chunk = [&](int kc) {
 #pragma unroll
-        for (int r = 0; r < ET; ++r) {
-            int c = tid + 256 * r;
-            int row = c >> 3, kch = c & 7;
-            wreg[r] = *reinterpret_cast<const bf16x8*>(Wgt + (size_t)row * d + kc * GATE_BK + kch * 8);
+        for (int r = 0; r < CPT; ++r) {
+            const int c = tid + NT * r;
+            const int krow = c / (E_PAD / 8), ech = c % (E_PAD / 8);
+            u32x4 v = {0u, 0u, 0u, 0u};
+            if (c < CHUNKS && ech * 8 < e)  // e % 8 == 0: a chunk is all experts or all padding
+                v = *reinterpret_cast<const u32x4*>(Wg + (size_t)(kc * GATE_BK + krow) * e + ech * 8);
+            wreg[r] = v;
         }
 #pragma unroll
-        for (int s = 0; s < 4; ++s)
-            xreg[s] = *reinterpret_cast<const bf16x8*>(xrow + kc * GATE_BK + s * 8);
+        for (int s = 0; s < 4; ++s) xreg[s] = *reinterpret_cast<const bf16x8*>(xrow + kc * GATE_BK + s * 8);
     };
 
+    // The contraction index of a stage is consumed in the order (half, step): lanes 0-31 own elements
+    // [0,32) of the stage, lanes 32-63 own [32,64), so a lane's X values are 64 contiguous bytes.
+    const int w_frag = (half * 32 + (l16 >> 2)) * PITCH + ((lane >> 4) & 1) * 16 + (l16 & 3) * 4;
     const int nk = d / GATE_BK;
     load_chunk(0);
     for (int kc = 0; kc < nk; ++kc) {
         __syncthreads();
 #pragma unroll
-        for (int r = 0; r < ET; ++r) {
-            int c = tid + 256 * r;
-            int row = c >> 3, kch = c & 7;
-            *reinterpret_cast<bf16x8*>(&Wt[row * GATE_LDS_STRIDE + kch * 8]) = wreg[r];
+        for (int r = 0; r < CPT; ++r) {
+            const int c = tid + NT * r;
+            const int krow = c / (E_PAD / 8), ech = c % (E_PAD / 8);
+            if (c < CHUNKS) *reinterpret_cast<u32x4*>(&Wk[krow * PITCH + ech * 8]) = wreg[r];
         }
         __syncthreads();
         bf16x8 xcur[4];
 #pragma unroll
         for (int s = 0; s < 4; ++s) xcur[s] = xreg[s];
         if (kc + 1 < nk) load_chunk(kc + 1);
-        // The contraction index is consumed in the order (half, s): lanes 0-31 own
-        // elements [0,32) of the stage, lanes 32-63 own [32,64); both operands agree.
 #pragma unroll
         for (int s = 0; s < 4; ++s) {
 #pragma unroll
             for (int te = 0; te < ET; ++te) {
-                bf16x8 a = *reinterpret_cast<const bf16x8*>(
-                    &Wt[(te * 32 + col) * GATE_LDS_STRIDE + half * 32 + s * 8]);
+                const bf16_t* p0 = &Wk[w_frag + s * 8 * PITCH + te * 32];
+                bf16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4bf16((lds_bf16x4*)(p0));
+                bf16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4bf16((lds_bf16x4*)(p0 + 4 * PITCH));
+                bf16x8 a = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
                 acc[te] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, xcur[s], acc[te], 0, 0, 0);
             }
         }
@@ -122,7 +118,6 @@ gate_mfma_kernel(const bf16_t* __restrict__ X, const bf16_t* __restrict__ Wgt,
         }
     sum += __shfl_xor(sum, 32, kWave);
     if (tok >= n) return;
-    const bool s_vec = (S != nullptr) && ((e & 3) == 0);
 #pragma unroll
     for (int te = 0; te < ET; ++te)
 #pragma unroll
@@ -131,24 +126,21 @@ gate_mfma_kernel(const bf16_t* __restrict__ X, const bf16_t* __restrict__ Wgt,
             float v[4];
 #pragma unroll
             for (int j = 0; j < 4; ++j) v[j] = acc[te][4 * q + j] / sum;
+            if (ex0 >= e) continue;  // e % 8 == 0: a quad is all experts or all padding
             if (St != nullptr) {
 #pragma unroll
-                for (int j = 0; j < 4; ++j)
-                    if (ex0 + j < e) St[(size_t)(ex0 + j) * n + tok] = v[j];
+                for (int j = 0; j < 4; ++j) St[(size_t)(ex0 + j) * n + tok] = v[j];
             }
             if (S != nullptr) {
-                if (s_vec) {
-                    if (ex0 < e) {
-                        floatx4 o = {v[0], v[1], v[2], v[3]};
-                        *reinterpret_cast<floatx4*>(S + (size_t)tok * e + ex0) = o;
-                    }
-                } else {
-#pragma unroll
-                    for (int j = 0; j < 4; ++j)
-                        if (ex0 + j < e) S[(size_t)tok * e + ex0 + j] = v[j];
-                }
+                floatx4 o = {v[0], v[1], v[2], v[3]};
+                *reinterpret_cast<floatx4*>(S + (size_t)tok * e + ex0) = o;
             }
         }
+}
+
+__global__ void __launch_bounds__(256)
+zero_words_kernel(uint32_t* __restrict__ p, long long count) {
+    for (long long i = (long long)blockIdx.x * 256 + threadIdx.x; i < count; i += (long long)gridDim.x * 256) p[i] = 0u;
 }
 
 // ---------------------------------------------------------------------------
@@ -199,26 +191,34 @@ gate_generic_kernel(const T* __restrict__ X, const T* __restrict__ Wg, float* __
 }
 
 int launch_gate(const void* X, const void* Wg, float* S, float* St, int64_t n, int64_t d, int64_t e,
-                int dtype, void* wgt_ws, hipStream_t stream) {
-    const bool mfma = dtype == EC_BF16 && (d % GATE_BK) == 0 && e <= 256 && wgt_ws != nullptr;
+                int dtype, uint32_t* zero_buf, int64_t zero_words, hipStream_t stream) {
+    const bool mfma = dtype == EC_BF16 && (d % GATE_BK) == 0 && e <= 256 && (e % 8) == 0;
     if (mfma) {
-        int et = e <= 32 ? 1 : e <= 64 ? 2 : e <= 128 ? 4 : 8;
-        int e_pad = 32 * et;
-        dim3 tg((unsigned)ceil_div(d, 32), (unsigned)(e_pad / 32));
-        hipLaunchKernelGGL(wg_transpose_kernel, tg, dim3(256), 0, stream, (const bf16_t*)Wg, (bf16_t*)wgt_ws,
-                           (int)d, (int)e, e_pad);
-        dim3 grid((unsigned)ceil_div(n, 128));
-#define EC_GATE_LAUNCH(ETV)                                                                              \
-    hipLaunchKernelGGL(gate_mfma_kernel<ETV>, grid, dim3(256), 0, stream, (const bf16_t*)X,              \
-                       (const bf16_t*)wgt_ws, S, St, (int)n, (int)d, (int)e)
-        switch (et) {
-            case 1: EC_GATE_LAUNCH(1); break;
-            case 2: EC_GATE_LAUNCH(2); break;
-            case 4: EC_GATE_LAUNCH(4); break;
-            default: EC_GATE_LAUNCH(8); break;
+        const int et = e <= 32 ? 1 : e <= 64 ? 2 : e <= 128 ? 4 : 8;
+        // one wavefront per block while that still leaves blocks for every compute unit, four otherwise
+        const bool small = n <= 32 * 1024 && et <= 2;
+        const int tok_per_block = small ? 32 : 128;
+        dim3 grid((unsigned)ceil_div(n, tok_per_block));
+#define EC_GATE_LAUNCH(ETV, NWV)                                                                          \
+    hipLaunchKernelGGL((gate_mfma_kernel<ETV, NWV>), grid, dim3(64 * NWV), 0, stream, (const bf16_t*)X,   \
+                       (const bf16_t*)Wg, S, St, (int)n, (int)d, (int)e, zero_buf, (int)zero_words)
+        if (small) {
+            if (et == 1) EC_GATE_LAUNCH(1, 1); else EC_GATE_LAUNCH(2, 1);
+        } else {
+            switch (et) {
+                case 1: EC_GATE_LAUNCH(1, 4); break;
+                case 2: EC_GATE_LAUNCH(2, 4); break;
+                case 4: EC_GATE_LAUNCH(4, 4); break;
+                default: EC_GATE_LAUNCH(8, 4); break;
+            }
         }
 #undef EC_GATE_LAUNCH
         return check_launch();
+    }
+    if (zero_words > 0) {
+        long long zb = (zero_words + 255) / 256;
+        hipLaunchKernelGGL(zero_words_kernel, dim3((unsigned)(zb > 4096 ? 4096 : zb)), dim3(256), 0, stream, zero_buf,
+                           (long long)zero_words);
     }
     int64_t blocks = ceil_div(n, 4);
     if (blocks > 65536) blocks = 65536;

@@ -2,50 +2,63 @@
 //
 // One 1024-thread workgroup per expert works on that expert's row of S^T
 // (n contiguous floats).  Scores are non-negative, so their bit patterns order
-// like unsigned integers.  Steps:
+// like unsigned integers, and (score bits, ~token) is a total order in which
+// "larger" means "admitted first".  Steps:
 //   1. stage the row in LDS when it fits (one HBM read), find min and max;
 //   2. radix-select on (bits - min), 8 bits per pass starting at the top bit of
 //      the actual range, until the bin holding the k-th score has at most
-//      TOPK_CAND_MAX members (usually one or two passes);
-//   3. compact the surely selected scores and the candidates into 64-bit keys
-//      (score bits << 32 | ~token), wavefront-aggregated slot allocation;
-//      if all bits are used up and too many candidates remain they are exact
-//      ties: admit them in token order with ballot prefix ranks instead;
-//   4. bitonic sort of the keys, descending: score descending, then token
-//      ascending -- the order the interface promises -- and write the first k.
+//      TOPK_CAND_MAX members or all 32 bits are decided;
+//   3. find the cut-off key, the k-th largest (score, ~token): among few
+//      candidates by counting, among many exact ties by token order;
+//   4. every wavefront owns a contiguous range of tokens: count the admitted
+//      ones per range, prefix the counts, then write the bucket in ascending
+//      token order with ballot ranks.  No sort is needed.
 #include "ec_common.h"
 
 namespace ecmoe {
 
 constexpr int TOPK_THREADS = 1024;
 constexpr int TOPK_WAVES = TOPK_THREADS / kWave;
-constexpr int TOPK_CAND_MAX = 1024;
+constexpr int TOPK_CAND_MAX = 256;
 
-__host__ __device__ inline int64_t topk_next_pow2(int64_t v) {
-    int64_t p = 1;
-    while (p < v) p <<= 1;
-    return p;
-}
+// Optional token-major by-products for the combine stage, written while the bucket is emitted:
+// either a slot list per token (slot_cnt[l] counts the experts that chose token l, the first
+// `slot_cap` of them leave their bucket row i*k+j in slots[l*slot_cap + ...], in arrival order)
+// or one bit per (token, expert) in `bitmap` (`bitmap_words` 32-bit words per token).
+// Integer atomics only: the set of entries does not depend on the order of arrival.
+struct TopkEmit {
+    int32_t* slot_cnt;
+    int32_t* slots;
+    int slot_cap;
+    uint32_t* bitmap;
+    int bitmap_words;
+};
 
-// Capacity (in keys) of the sort buffer for bucket size k over n tokens.
-__host__ __device__ inline int64_t topk_key_capacity(int64_t n, int64_t k) {
-    int64_t m = k + TOPK_CAND_MAX;
-    if (m > n) m = n;  // never more keys than tokens
-    if (m < 2) m = 2;
-    return topk_next_pow2(m);
+__device__ __forceinline__ void topk_emit(const TopkEmit& em, int expert, int k, int rank, int tok) {
+    if (em.slot_cnt != nullptr) {
+        int s = atomicAdd(&em.slot_cnt[tok], 1);
+        if (s < em.slot_cap) em.slots[(size_t)tok * em.slot_cap + s] = expert * k + rank;
+    }
+    if (em.bitmap != nullptr) atomicOr(&em.bitmap[(size_t)tok * em.bitmap_words + (expert >> 5)], 1u << (expert & 31));
 }
 
 struct TopkShared {
     unsigned int hist[256];
     unsigned int red[2 * TOPK_WAVES];
     unsigned int wave_cnt[TOPK_WAVES];
-    unsigned int bin, remaining, cand, slot;
+    unsigned long long cand[TOPK_CAND_MAX];
+    unsigned long long cutoff;
+    unsigned int bin, remaining, ncand, slot;
 };
 
-template <bool STAGED, bool KEYS_LDS>
+__device__ __forceinline__ unsigned long long topk_key(unsigned int bits, unsigned int tok) {
+    return ((unsigned long long)bits << 32) | (unsigned long long)(0xFFFFFFFFu - tok);
+}
+
+template <bool STAGED>
 __global__ void __launch_bounds__(TOPK_THREADS)
-topk_tokens_kernel(const float* __restrict__ St, int n, int k, int kcap, float* __restrict__ G,
-                   int32_t* __restrict__ I, unsigned long long* __restrict__ keys_ws, int stage_words) {
+topk_tokens_kernel(const float* __restrict__ St, int n, int k, float* __restrict__ G, int32_t* __restrict__ I,
+                   TopkEmit emit) {
     extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
     __shared__ TopkShared sh;
 
@@ -53,9 +66,6 @@ topk_tokens_kernel(const float* __restrict__ St, int n, int k, int kcap, float* 
     const int expert = blockIdx.x;
     const unsigned int* __restrict__ colg = reinterpret_cast<const unsigned int*>(St) + (size_t)expert * n;
     unsigned int* cols = reinterpret_cast<unsigned int*>(smem);
-    unsigned long long* keys = KEYS_LDS
-        ? reinterpret_cast<unsigned long long*>(smem + (STAGED ? (size_t)stage_words * 4 : 0))
-        : keys_ws + (size_t)expert * kcap;
 
     // ---- 1. stage + min/max ------------------------------------------------
     unsigned int vmin = 0xFFFFFFFFu, vmax = 0u;
@@ -119,97 +129,126 @@ topk_tokens_kernel(const float* __restrict__ St, int n, int k, int kcap, float* 
                 else { b = 0; ab = a0; hb = h0; }
                 sh.bin = 4 * lane + b;
                 sh.remaining = remaining - ab;
-                sh.cand = hb;
+                sh.ncand = hb;
             }
         }
         __syncthreads();
         prefix |= sh.bin << nlo;
         remaining = sh.remaining;
-        cand = sh.cand;
+        cand = sh.ncand;
         lo = nlo;
         __syncthreads();
     }
     const unsigned int hmask = lo >= 32 ? 0u : ~((1u << lo) - 1u);
-    const unsigned int n_sure = (unsigned int)k - remaining;  // scores strictly above the candidate bin
-    const bool take_all_cand = (unsigned long long)n_sure + cand <= (unsigned long long)kcap;
 
-    // ---- 3. compaction into keys ------------------------------------------
-    if (tid == 0) sh.slot = 0;
-    __syncthreads();
-    const int n_round = (n + TOPK_THREADS - 1) / TOPK_THREADS * TOPK_THREADS;
-    for (int idx = tid; idx < n_round; idx += TOPK_THREADS) {
-        bool sel = false;
-        unsigned int v = 0;
-        if (idx < n) {
-            v = ld(idx);
-            unsigned int hk = (v - vmin) & hmask;
-            sel = hk > prefix || (take_all_cand && hk == prefix);
+    // Token range of every wavefront (multiple of 64 so chunks stay aligned).
+    const int per_wave = ((n + TOPK_WAVES - 1) / TOPK_WAVES + kWave - 1) / kWave * kWave;
+    const int w_beg = wave * per_wave;
+    const int w_end = (w_beg + per_wave) < n ? (w_beg + per_wave) : n;
+
+    // ---- 3. the cut-off key ---------------------------------------------------
+    if (cand <= (unsigned int)TOPK_CAND_MAX) {
+        // Few candidates: gather their keys, then the one with exactly remaining-1 keys above it is the cut-off.
+        if (tid == 0) sh.slot = 0;
+        __syncthreads();
+        const int n_round = (n + TOPK_THREADS - 1) / TOPK_THREADS * TOPK_THREADS;
+        for (int idx = tid; idx < n_round; idx += TOPK_THREADS) {
+            bool is_cand = false;
+            unsigned int v = 0;
+            if (idx < n) {
+                v = ld(idx);
+                is_cand = ((v - vmin) & hmask) == prefix;
+            }
+            unsigned long long bal = __ballot(is_cand);
+            unsigned int base = 0;
+            if (bal != 0ull) {
+                if (lane == 0) base = atomicAdd(&sh.slot, (unsigned int)__popcll(bal));
+                base = __shfl(base, 0, kWave);
+            }
+            if (is_cand) sh.cand[base + __popcll(bal & ((1ull << lane) - 1ull))] = topk_key(v, (unsigned int)idx);
         }
-        unsigned long long bal = __ballot(sel);
-        unsigned int base = 0;
-        if (bal != 0ull) {
-            if (lane == 0) base = atomicAdd(&sh.slot, (unsigned int)__popcll(bal));
-            base = __shfl(base, 0, kWave);
+        __syncthreads();
+        if (tid < (int)cand) {
+            const unsigned long long mine = sh.cand[tid];
+            const unsigned int mhi = (unsigned int)(mine >> 32), mlo = (unsigned int)mine;
+            unsigned int above = 0;
+            for (unsigned int j = 0; j < cand; ++j) {
+                const unsigned long long o = sh.cand[j];
+                const unsigned int ohi = (unsigned int)(o >> 32), olo = (unsigned int)o;
+                above += (ohi > mhi) | ((ohi == mhi) & (olo > mlo));
+            }
+            if (above == remaining - 1u) sh.cutoff = mine;
         }
-        if (sel) {
-            unsigned int slot = base + __popcll(bal & ((1ull << lane) - 1ull));
-            keys[slot] = ((unsigned long long)v << 32) | (unsigned long long)(0xFFFFFFFFu - (unsigned int)idx);
+    } else {
+        // All 32 bits decided and still many candidates: exact ties at the threshold score.  The cut-off is
+        // the `remaining`-th tied token in token order.
+        const unsigned int tbits = prefix + vmin;
+        unsigned int ties = 0;
+        for (int base = w_beg; base < w_end; base += kWave) {
+            int idx = base + lane;
+            bool eq = idx < w_end && ld(idx) == tbits;
+            ties += (unsigned int)__popcll(__ballot(eq));
         }
-    }
-    __syncthreads();
-    unsigned int m = sh.slot;  // keys written so far
-    if (!take_all_cand) {
-        // Exact ties at the threshold (all 32 bits equal): admit the first `remaining` in token order.
-        unsigned int running = 0;
-        for (int idx0 = 0; idx0 < n && running < remaining; idx0 += TOPK_THREADS) {
-            int idx = idx0 + tid;
-            bool eq = idx < n && ((ld(idx) - vmin) == prefix);
-            unsigned long long bal = __ballot(eq);
-            if (lane == 0) sh.wave_cnt[wave] = (unsigned int)__popcll(bal);
-            __syncthreads();
-            unsigned int before = 0, total = 0;
+        if (lane == 0) sh.wave_cnt[wave] = ties;
+        __syncthreads();
+        unsigned int before = 0;
 #pragma unroll
-            for (int w = 0; w < TOPK_WAVES; ++w) {
-                unsigned int c = sh.wave_cnt[w];
-                before += w < wave ? c : 0u;
-                total += c;
+        for (int w = 0; w < TOPK_WAVES; ++w) before += w < wave ? sh.wave_cnt[w] : 0u;
+        if (before < remaining && remaining <= before + ties) {  // this wavefront holds the cut-off token
+            unsigned int seen = before;
+            for (int base = w_beg; base < w_end; base += kWave) {
+                int idx = base + lane;
+                bool eq = idx < w_end && ld(idx) == tbits;
+                unsigned long long bal = __ballot(eq);
+                unsigned int c = (unsigned int)__popcll(bal);
+                if (seen + c >= remaining) {
+                    unsigned int rank = seen + (unsigned int)__popcll(bal & ((1ull << lane) - 1ull));
+                    if (eq && rank == remaining - 1u) sh.cutoff = topk_key(tbits, (unsigned int)idx);
+                    break;
+                }
+                seen += c;
             }
-            unsigned int rank = running + before + (unsigned int)__popcll(bal & ((1ull << lane) - 1ull));
-            if (eq && rank < remaining)
-                keys[n_sure + rank] = ((unsigned long long)(prefix + vmin) << 32) |
-                                      (unsigned long long)(0xFFFFFFFFu - (unsigned int)idx);
-            running += total;
-            __syncthreads();
         }
-        m = (unsigned int)k;
     }
-
-    // ---- 4. bitonic sort, descending --------------------------------------
-    unsigned int mp = 2;
-    while (mp < m) mp <<= 1;
-    for (unsigned int idx = m + tid; idx < mp; idx += TOPK_THREADS) keys[idx] = 0ull;  // below every real key
     __syncthreads();
-    for (unsigned int size = 2; size <= mp; size <<= 1) {
-        for (unsigned int stride = size >> 1; stride > 0; stride >>= 1) {
-            for (unsigned int p = tid; p < (mp >> 1); p += TOPK_THREADS) {
-                unsigned int lo_i = 2 * p - (p & (stride - 1));  // index with the `stride` bit clear
-                unsigned int hi_i = lo_i + stride;
-                bool desc = (lo_i & size) == 0;
-                unsigned long long a = keys[lo_i], b = keys[hi_i];
-                if ((a < b) == desc) { keys[lo_i] = b; keys[hi_i] = a; }
-            }
-            if (!KEYS_LDS) __threadfence_block();
-            __syncthreads();
-        }
+    const unsigned long long cutoff = sh.cutoff;
+    const unsigned int chi = (unsigned int)(cutoff >> 32), clo = (unsigned int)cutoff;
+    auto admitted = [&](unsigned int v, int idx) -> bool {
+        const unsigned int klo = 0xFFFFFFFFu - (unsigned int)idx;
+        return (v > chi) | ((v == chi) & (klo >= clo));
+    };
+
+    // ---- 4. count per wavefront range, prefix, emit in token order ------------
+    unsigned int mine_cnt = 0;
+    for (int base = w_beg; base < w_end; base += kWave) {
+        int idx = base + lane;
+        bool sel = idx < w_end && admitted(ld(idx), idx);
+        mine_cnt += (unsigned int)__popcll(__ballot(sel));
     }
-    for (int j = tid; j < k; j += TOPK_THREADS) {
-        unsigned long long key = keys[j];
-        G[(size_t)expert * k + j] = __uint_as_float((unsigned int)(key >> 32));
-        I[(size_t)expert * k + j] = (int32_t)(0xFFFFFFFFu - (unsigned int)(key & 0xFFFFFFFFull));
+    __syncthreads();  // wave_cnt may still be read by the tie path above
+    if (lane == 0) sh.wave_cnt[wave] = mine_cnt;
+    __syncthreads();
+    unsigned int pos = 0;
+#pragma unroll
+    for (int w = 0; w < TOPK_WAVES; ++w) pos += w < wave ? sh.wave_cnt[w] : 0u;
+    for (int base = w_beg; base < w_end; base += kWave) {
+        int idx = base + lane;
+        unsigned int v = idx < w_end ? ld(idx) : 0u;
+        bool sel = idx < w_end && admitted(v, idx);
+        unsigned long long bal = __ballot(sel);
+        if (sel) {
+            const unsigned int j = pos + (unsigned int)__popcll(bal & ((1ull << lane) - 1ull));
+            if (j < (unsigned int)k) {  // always true for a correct selection; guards the stores
+                G[(size_t)expert * k + j] = __uint_as_float(v);
+                I[(size_t)expert * k + j] = idx;
+                topk_emit(emit, expert, k, (int)j, idx);
+            }
+        }
+        pos += (unsigned int)__popcll(bal);
     }
 }
 
-// LDS the top-k kernel may use for the staged row plus the keys.
+// LDS the top-k kernel may use for the staged row.
 static size_t topk_lds_budget() {
     static size_t budget = 0;
     if (budget == 0) {
@@ -225,40 +264,29 @@ static size_t topk_lds_budget() {
     return budget;
 }
 
-// Sort keys that do not fit in LDS live in the workspace: bytes for all experts (0 when LDS suffices).
-size_t topk_ws_bytes(int64_t n, int64_t e, int64_t k) {
-    // Sized for the smallest LDS any supported device offers (64 KiB) so that the
-    // workspace size does not depend on the device that later runs the call.
-    int64_t kcap = topk_key_capacity(n, k);
-    if ((size_t)kcap * 8 <= 48 * 1024) return 0;
-    return (size_t)e * (size_t)kcap * 8;
-}
+// The selection needs no scratch in global memory.
+size_t topk_ws_bytes(int64_t, int64_t, int64_t) { return 0; }
 
 int launch_topk(const float* St, int64_t n, int64_t e, int64_t k, float* G, int32_t* I,
-                unsigned long long* sortkeys_ws, hipStream_t stream) {
-    const int64_t kcap = topk_key_capacity(n, k);
-    const size_t budget = topk_lds_budget();
-    const size_t key_bytes = (size_t)kcap * 8;
-    const bool keys_lds = key_bytes <= 48 * 1024;  // same rule as topk_ws_bytes
+                unsigned long long* sortkeys_ws, int32_t* slot_cnt, int32_t* slots, int slot_cap, uint32_t* bitmap,
+                hipStream_t stream) {
+    (void)sortkeys_ws;
+    TopkEmit emit;
+    emit.slot_cnt = slot_cnt; emit.slots = slots; emit.slot_cap = slot_cap;
+    emit.bitmap = bitmap; emit.bitmap_words = (int)ceil_div(e, 32);
     const size_t stage_bytes = align_up((size_t)n * 4, 16);
-    const bool staged = stage_bytes + (keys_lds ? key_bytes : 0) <= budget;
-    size_t dyn = (staged ? stage_bytes : 0) + (keys_lds ? key_bytes : 0);
-    if (!keys_lds && sortkeys_ws == nullptr) return EC_ERR_WORKSPACE;
+    const bool staged = stage_bytes <= topk_lds_budget();
+    const size_t dyn = staged ? stage_bytes : 0;
     dim3 grid((unsigned)e), block(TOPK_THREADS);
-#define EC_TOPK_LAUNCH(ST, KL)                                                                             \
-    do {                                                                                                   \
-        auto kern = topk_tokens_kernel<ST, KL>;                                                            \
-        if (dyn > 64 * 1024)                                                                               \
-            (void)hipFuncSetAttribute(reinterpret_cast<const void*>(kern),                                 \
-                                      hipFuncAttributeMaxDynamicSharedMemorySize, (int)dyn);               \
-        hipLaunchKernelGGL(kern, grid, block, dyn, stream, St, (int)n, (int)k, (int)kcap, G, I,            \
-                           sortkeys_ws, (int)(stage_bytes / 4));                                           \
-    } while (0)
-    if (staged && keys_lds) EC_TOPK_LAUNCH(true, true);
-    else if (staged) EC_TOPK_LAUNCH(true, false);
-    else if (keys_lds) EC_TOPK_LAUNCH(false, true);
-    else EC_TOPK_LAUNCH(false, false);
-#undef EC_TOPK_LAUNCH
+    if (staged) {
+        auto kern = topk_tokens_kernel<true>;
+        if (dyn > 64 * 1024)
+            (void)hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
+                                      (int)dyn);
+        hipLaunchKernelGGL(kern, grid, block, dyn, stream, St, (int)n, (int)k, G, I, emit);
+    } else {
+        hipLaunchKernelGGL(topk_tokens_kernel<false>, grid, block, 0, stream, St, (int)n, (int)k, G, I, emit);
+    }
     return check_launch();
 }
 
