@@ -130,7 +130,7 @@ int ec_moe_expert_ffn(const void* Xin, const void* W1, const void* W2, void* Xe,
         if (!ws_ok(ws, ws_bytes, need)) return EC_ERR_WORKSPACE;
         H = ws;
     }
-    return launch_ffn(Xin, W1, W2, Xe, A_save, H, e, k, d, d_ff, act, dtype, (hipStream_t)stream);
+    return launch_ffn(Xin, nullptr, nullptr, 0, W1, W2, Xe, A_save, H, e, k, d, d_ff, act, dtype, (hipStream_t)stream);
 }
 
 int ec_moe_combine(const void* Xe, const float* G, const int32_t* I, void* Xout, int64_t n, int64_t d, int64_t e,
@@ -186,13 +186,17 @@ int ec_moe_forward(const void* X, const void* Wg, const void* W1, const void* W2
     rc = launch_topk(St, n, e, k, G, I, (unsigned long long*)at(ws, L.sortkeys), ix.use_slots ? ix.slot_cnt : nullptr,
                      ix.slots, ix.slot_cap, ix.use_slots ? nullptr : ix.bitmap, st);
     if (rc != EC_OK) return rc;
-    rc = launch_dispatch(X, I, Xin, n, d, e, k, dtype, st);
-    if (rc != EC_OK) return rc;
+    // The bucket gather is fused into the first expert product unless the caller wants X_in itself.
+    const bool fused_gather = !identity && Xin_out == nullptr && ffn_can_gather(dtype, n, k, d, d_ff);
+    if (!fused_gather) {
+        rc = launch_dispatch(X, I, Xin, n, d, e, k, dtype, st);
+        if (rc != EC_OK) return rc;
+    }
     const void* Xe = Xin;  // identity experts
     if (!identity) {
         void* H = H_out ? H_out : at(ws, L.h);
         void* Xe_w = Xe_out ? Xe_out : at(ws, L.xe);
-        rc = launch_ffn(Xin, W1, W2, Xe_w, A_out, H, e, k, d, d_ff, act, dtype, st);
+        rc = launch_ffn(fused_gather ? nullptr : Xin, X, I, n, W1, W2, Xe_w, A_out, H, e, k, d, d_ff, act, dtype, st);
         if (rc != EC_OK) return rc;
         Xe = Xe_w;
     }

@@ -9,6 +9,7 @@
 //    are then read as 16-byte contraction-contiguous vectors.
 //  * fp32: plain FMA tiles (small parity configuration only).
 #include <cmath>
+#include <cstdlib>
 
 #include "ec_common.h"
 
@@ -239,7 +240,8 @@ __device__ __forceinline__ float apply_act_bf16(float a) {
 template <int BM, int BN, int STAGES, int OCC, int ACT, bool SAVE_PRE>
 __global__ void __launch_bounds__(256, OCC)
 gemm_bf16_fast_kernel(const bf16_t* __restrict__ Aall, const bf16_t* __restrict__ Ball, bf16_t* __restrict__ Call,
-                      bf16_t* __restrict__ Cpreall, int M, int N, int K, int G, int tiles_m, int tiles_n) {
+                      bf16_t* __restrict__ Cpreall, int M, int N, int K, int G, int tiles_m, int tiles_n,
+                      const int32_t* __restrict__ gather, int gather_rows) {
     constexpr int WM = BM / 2, WN = BN / 2;
     constexpr int TM = WM / 32, TN = WN / 32;
     constexpr int A_CHUNKS = BM * 8 / 256;              // 16-byte chunks of the A tile per thread
@@ -270,11 +272,13 @@ gemm_bf16_fast_kernel(const bf16_t* __restrict__ Aall, const bf16_t* __restrict_
     const int wr = wave >> 1, wc = wave & 1;
     const int col = lane & 31, half = lane >> 5;
 
-    const int lg = g, lm0 = m0, ln0 = n0;
-    const __amdgpu_buffer_rsrc_t rsrcA = __builtin_amdgcn_make_buffer_rsrc(
-        const_cast<bf16_t*>(Aall + (size_t)lg * M * K), 0, M * K * 2, 0x00020000);
+    // With `gather`, row m of group g's left operand is row gather[g*M + m] of one shared
+    // [gather_rows, K] matrix (the dispatch of Eq. 3 fused into the tile loads).
+    const __amdgpu_buffer_rsrc_t rsrcA = gather != nullptr
+        ? __builtin_amdgcn_make_buffer_rsrc(const_cast<bf16_t*>(Aall), 0, gather_rows * K * 2, 0x00020000)
+        : __builtin_amdgcn_make_buffer_rsrc(const_cast<bf16_t*>(Aall + (size_t)g * M * K), 0, M * K * 2, 0x00020000);
     const __amdgpu_buffer_rsrc_t rsrcB = __builtin_amdgcn_make_buffer_rsrc(
-        const_cast<bf16_t*>(Ball + (size_t)lg * K * N), 0, K * N * 2, 0x00020000);
+        const_cast<bf16_t*>(Ball + (size_t)g * K * N), 0, K * N * 2, 0x00020000);
 
     // Per-thread byte offsets inside the expert's matrices (the stage offset is added as a scalar).
     // A tile: 8 lanes cover one 128-byte row segment.  B tile: BN/8 lanes cover one whole row of
@@ -284,7 +288,12 @@ gemm_bf16_fast_kernel(const bf16_t* __restrict__ Aall, const bf16_t* __restrict_
     for (int r = 0; r < A_CHUNKS; ++r) {
         int c = tid + 256 * r;
         int row = c >> 3, kch = c & 7;
-        a_voff[r] = ((lm0 + row) * K + kch * 8) * 2;
+        if (gather != nullptr) {
+            const int gm = m0 + row;  // rows past M point outside the buffer: they load zeros
+            a_voff[r] = gm < M ? (gather[(size_t)g * M + gm] * K + kch * 8) * 2 : 0x7FFFFF00;
+        } else {
+            a_voff[r] = ((m0 + row) * K + kch * 8) * 2;
+        }
         a_lds[r] = row * GEMM_LDS_STRIDE + kch * 8;
     }
     int b_voff[B_CHUNKS], b_lds[B_CHUNKS];
@@ -292,7 +301,7 @@ gemm_bf16_fast_kernel(const bf16_t* __restrict__ Aall, const bf16_t* __restrict_
     for (int r = 0; r < B_CHUNKS; ++r) {
         int c = tid + 256 * r;
         int krow = c / (BN / 8), nch = c % (BN / 8);
-        b_voff[r] = (krow * N + ln0 + nch * 8) * 2;
+        b_voff[r] = (krow * N + n0 + nch * 8) * 2;
         b_lds[r] = A_ELEMS + krow * B_PITCH + nch * 8;
     }
 
@@ -470,7 +479,7 @@ gemm_bf16_fast_kernel(const bf16_t* __restrict__ Aall, const bf16_t* __restrict_
 
 template <int BM, int BN, int STAGES, int OCC>
 static void launch_gemm_bf16(const bf16_t* A, const bf16_t* B, bf16_t* C, bf16_t* Cpre, int G, int M, int N, int K,
-                             int act, hipStream_t stream) {
+                             int act, const int32_t* gather, int gather_rows, hipStream_t stream) {
     const int tiles_m = (M + BM - 1) / BM, tiles_n = (N + BN - 1) / BN;
     const int total = G * tiles_m * tiles_n;
     dim3 grid((unsigned)((total + 7) / 8 * 8)), block(256);
@@ -489,7 +498,8 @@ static void launch_gemm_bf16(const bf16_t* A, const bf16_t* B, bf16_t* C, bf16_t
             if (lds > 64 * 1024)                                                                            \
                 (void)hipFuncSetAttribute(reinterpret_cast<const void*>(kern),                              \
                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);            \
-            hipLaunchKernelGGL(kern, grid, block, lds, stream, A, B, C, Cpre, M, N, K, G, tiles_m, tiles_n); \
+            hipLaunchKernelGGL(kern, grid, block, lds, stream, A, B, C, Cpre, M, N, K, G, tiles_m, tiles_n,     \
+                               gather, gather_rows);                                                        \
         } else {                                                                                            \
             auto kern = gemm_bf16_generic_kernel<BM, BN, ACTV, SAVE>;                                       \
             if (lds > 64 * 1024)                                                                            \
@@ -511,16 +521,28 @@ static void launch_gemm_bf16(const bf16_t* A, const bf16_t* B, bf16_t* C, bf16_t
 // Tile configuration of a grouped product: the candidate with the lowest estimated time, taken as
 // (rounds of 256 compute units) x (tile area) / (relative rate of that configuration).
 static void gemm_bf16_dispatch(const bf16_t* A, const bf16_t* B, bf16_t* C, bf16_t* Cpre, int G, int M, int N,
-                               int K, int act, hipStream_t stream) {
+                               int K, int act, const int32_t* gather, int gather_rows, hipStream_t stream) {
     auto cost = [&](int bm, int bn, int occ, double rate) {
         double tiles = (double)G * ((M + bm - 1) / bm) * ((N + bn - 1) / bn);
         double rounds = std::ceil(tiles / (256.0 * occ)) * occ;
         return rounds * bm * bn / rate;
     };
     const double c0 = cost(256, 256, 1, 1.0), c1 = cost(256, 128, 1, 0.85), c2 = cost(128, 128, 2, 0.6);
-    if (c0 <= c1 && c0 <= c2) launch_gemm_bf16<256, 256, 2, 1>(A, B, C, Cpre, G, M, N, K, act, stream);
-    else if (c1 <= c2) launch_gemm_bf16<256, 128, 2, 1>(A, B, C, Cpre, G, M, N, K, act, stream);
-    else launch_gemm_bf16<128, 128, 1, 2>(A, B, C, Cpre, G, M, N, K, act, stream);
+    int pick = (c0 <= c1 && c0 <= c2) ? 0 : (c1 <= c2 ? 1 : 2);
+    // Short contractions leave the epilogue (activation, stores) as large as the MFMA phase: two
+    // co-resident 256 x 128 workgroups per compute unit overlap one's epilogue with the other's MFMAs.
+    if (pick == 0 && K <= 1024 && cost(256, 128, 2, 1.0) <= 1.25 * c0) pick = 3;
+    static const int forced = [] {  // tuning knob: EC_MOE_GEMM_TILE=0..3 forces one configuration
+        const char* v = std::getenv("EC_MOE_GEMM_TILE");
+        return v ? std::atoi(v) : -1;
+    }();
+    if (forced >= 0 && forced <= 3) pick = forced;
+    switch (pick) {
+        case 0: launch_gemm_bf16<256, 256, 2, 1>(A, B, C, Cpre, G, M, N, K, act, gather, gather_rows, stream); break;
+        case 1: launch_gemm_bf16<256, 128, 2, 1>(A, B, C, Cpre, G, M, N, K, act, gather, gather_rows, stream); break;
+        case 2: launch_gemm_bf16<128, 128, 1, 2>(A, B, C, Cpre, G, M, N, K, act, gather, gather_rows, stream); break;
+        default: launch_gemm_bf16<256, 128, 1, 2>(A, B, C, Cpre, G, M, N, K, act, gather, gather_rows, stream); break;
+    }
 }
 
 // ===========================================================================
@@ -589,16 +611,28 @@ static void launch_gemm_f32(const float* A, const float* B, float* C, float* Cpr
 // ---------------------------------------------------------------------------
 // Xe = act(Xin.W1).W2 ; H is the [e,k,d_ff] hidden buffer (workspace or caller's).
 // ---------------------------------------------------------------------------
-int launch_ffn(const void* Xin, const void* W1, const void* W2, void* Xe, void* A_save, void* H,
-               int64_t e, int64_t k, int64_t d, int64_t d_ff, int act, int dtype, hipStream_t stream) {
+// True when the first product can gather its rows straight from X (no X_in buffer needed).
+bool ffn_can_gather(int dtype, int64_t n, int64_t k, int64_t d, int64_t d_ff) {
+    return dtype == EC_BF16 && (d % GEMM_BK) == 0 && n * d * 2 < ((int64_t)1 << 31) - 65536 &&
+           d * d_ff * 2 < ((int64_t)1 << 31) && k > 0;
+}
+
+// Xin == nullptr: gather mode, rows of the buckets are read from X through I (needs ffn_can_gather).
+int launch_ffn(const void* Xin, const void* X, const int32_t* I, int64_t n, const void* W1, const void* W2, void* Xe,
+               void* A_save, void* H, int64_t e, int64_t k, int64_t d, int64_t d_ff, int act, int dtype,
+               hipStream_t stream) {
     const int G = (int)e, M = (int)k;
     if (dtype == EC_BF16) {
-        gemm_bf16_dispatch((const bf16_t*)Xin, (const bf16_t*)W1, (bf16_t*)H, (bf16_t*)A_save, G, M, (int)d_ff, (int)d,
-                           act, stream);
+        if (Xin == nullptr)
+            gemm_bf16_dispatch((const bf16_t*)X, (const bf16_t*)W1, (bf16_t*)H, (bf16_t*)A_save, G, M, (int)d_ff, (int)d,
+                               act, I, (int)n, stream);
+        else
+            gemm_bf16_dispatch((const bf16_t*)Xin, (const bf16_t*)W1, (bf16_t*)H, (bf16_t*)A_save, G, M, (int)d_ff,
+                               (int)d, act, nullptr, 0, stream);
         int rc = check_launch();
         if (rc != EC_OK) return rc;
         gemm_bf16_dispatch((const bf16_t*)H, (const bf16_t*)W2, (bf16_t*)Xe, nullptr, G, M, (int)d, (int)d_ff,
-                           EC_ACT_IDENTITY, stream);
+                           EC_ACT_IDENTITY, nullptr, 0, stream);
         return check_launch();
     }
     launch_gemm_f32((const float*)Xin, (const float*)W1, (float*)H, (float*)A_save, G, M, (int)d_ff, (int)d, act,
