@@ -40,6 +40,9 @@ def parse_args():
     ap.add_argument("--warmup", type=int, default=10)
     ap.add_argument("--workload", default="cfg2", help="cfg2 (headline), cfg3, cfg5")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--copy-calibration", type=int, default=0, metavar="MiB",
+                    help="only run a plain device-to-device copy of this many MiB five times (reference "
+                         "reading for the FETCH_SIZE / WRITE_SIZE counters) and exit")
     return ap.parse_args()
 
 
@@ -60,6 +63,16 @@ def main() -> int:
         print("bench.py: no GPU visible", file=sys.stderr)
         return 2
     m.lib()  # fails loudly when the HIP library is missing
+
+    if args.copy_calibration > 0:
+        nbytes = args.copy_calibration << 20
+        src = torch.ones(nbytes, dtype=torch.uint8, device="cuda")
+        dst = torch.empty_like(src)
+        for _ in range(5):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        print(json.dumps({"copy_calibration_bytes": nbytes, "copies": 5}))
+        return 0
 
     w = wl.WORKLOADS[args.workload]
     n, d, e, k, d_ff = w.n, w.d, w.e, w.k, w.d_ff

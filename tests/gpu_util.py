@@ -43,3 +43,23 @@ def torch_dtype(w: wl.Workload):
 # without intermediate rounding), scores S always fp32
 def out_tol(w: wl.Workload) -> float:
     return 2e-2 if w.dtype == wl.DTYPE_BF16 else 1e-5
+
+
+def score_tolerance(X: np.ndarray, Wg: np.ndarray) -> np.ndarray:
+    """Per-token relative tolerance on the fp32 scores S.
+
+    A logit is a length-d sum accumulated in fp32, so its absolute error is bounded to first order
+    by a small multiple of u * sum_t |x_t w_t| (u = 2^-24), and a relative error of S equals an
+    absolute error of (logit - logsumexp).  The bar is the stated 1e-5 plus 2u * max_i sum_t |x_t||w_ti|:
+    about 1.2e-5 for unit-variance tokens, and proportionally more for tokens scaled up to skew the
+    routing, whose logits are ten times larger.
+    """
+    a = np.abs(to_f64(X)) @ np.abs(to_f64(Wg))          # [n,e]
+    return 1e-5 + 2.0 * 2.0 ** -24 * a.max(axis=1)
+
+
+def max_rel_err_rows(got: np.ndarray, ref: np.ndarray) -> np.ndarray:
+    """Row-wise max |got - ref| / max(|ref|, rms(ref)) (rms over the whole tensor)."""
+    got, ref = to_f64(got), np.asarray(ref, dtype=np.float64)
+    rms = float(np.sqrt(np.mean(ref * ref)))
+    return (np.abs(got - ref) / np.maximum(np.abs(ref), max(rms, 1e-300))).max(axis=1)

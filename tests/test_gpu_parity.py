@@ -10,11 +10,11 @@ import pytest
 import torch
 
 import workloads as wl
-from gpu_util import max_rel_err, out_tol, to_dev, to_f64, to_host, torch_dtype
+from gpu_util import (max_rel_err, max_rel_err_rows, out_tol, score_tolerance, to_dev, to_f64, to_host,
+                      torch_dtype)
 
 pytestmark = pytest.mark.gpu
 
-S_TOL = 1e-5
 
 
 @pytest.fixture(scope="module")
@@ -36,8 +36,12 @@ def _p(msg):
     print(msg, flush=True)
 
 
-def _stagewise(m, ref, w, inp, check_ffn=True):
-    """Runs the layer stage by stage through the C ABI and checks each stage."""
+def _stagewise(m, ref, w, inp, check_ffn=True, ffn_experts=None):
+    """Runs the layer stage by stage through the C ABI and checks each stage.
+
+    ffn_experts: at full sizes the float64 oracle FFN is run on this sample of experts only
+    (experts are independent); the combine check then uses the GPU's X_e for the others.
+    """
     n, d, e, k = w.n, w.d, w.e, w.k
     dt = torch_dtype(w)
     ws = m.alloc_workspace(n, d, e, k, w.d_ff, w.dtype)
@@ -51,9 +55,10 @@ def _stagewise(m, ref, w, inp, check_ffn=True):
     S_h, St_h = to_host(S), to_host(St)
     assert (St_h == S_h.T).all()
     S_ref = ref.gate(inp["X"], inp["Wg"])
-    err = max_rel_err(S_h, S_ref)
-    _p(f"[{w.name}] S max rel err {err:.3e}")
-    assert err <= S_TOL
+    s_tol = score_tolerance(inp["X"], inp["Wg"])                  # per token, 1e-5 + fp32 accumulation bound
+    err_rows = max_rel_err_rows(S_h, S_ref)
+    _p(f"[{w.name}] S max rel err {err_rows.max():.3e} (worst ratio to its tolerance {(err_rows / s_tol).max():.2f})")
+    assert (err_rows <= s_tol).all()
     assert np.abs(S_h.astype(np.float64).sum(axis=1) - 1.0).max() < 1e-5 and (S_h >= 0).all()
 
     _p(f"[{w.name}] topk k={k}")
@@ -66,14 +71,14 @@ def _stagewise(m, ref, w, inp, check_ffn=True):
     assert (I_h == I_o).all()
     assert (G_h.view(np.uint32) == G_o.view(np.uint32)).all()
     # selections made on the oracle's own S differ only where scores are within rounding of the threshold
-    _, I_os = ref.topk_tokens(S_ref, k)
+    G_os, I_os = ref.topk_tokens(S_ref, k)
     diff = 0
     for i in range(e):
         flipped = np.array(sorted(set(I_os[i].tolist()) ^ set(I_h[i].tolist())), dtype=np.int64)
         diff += len(flipped) // 2
         if len(flipped):
-            thr = float(S_ref[I_os[i, -1], i])                    # the oracle's k-th score
-            assert (np.abs(S_ref[flipped, i].astype(np.float64) - thr) <= 2 * S_TOL * thr + 1e-30).all()
+            thr = float(G_os[i].min())                            # the oracle's k-th score
+            assert (np.abs(S_ref[flipped, i].astype(np.float64) - thr) <= 2 * s_tol[flipped] * thr + 1e-30).all()
     _p(f"[{w.name}] (expert, token) pairs differing from TopK(oracle S): {diff} of {e * k}")
 
     _p(f"[{w.name}] dispatch")
@@ -91,9 +96,10 @@ def _stagewise(m, ref, w, inp, check_ffn=True):
         torch.cuda.synchronize()
         Xe_h = to_host(Xe)
         if check_ffn:
-            Xe_ref = ref.expert_ffn(Xin_h, inp["W1"], inp["W2"], w.act)
-            err = max_rel_err(Xe_h, Xe_ref)
-            _p(f"[{w.name}] X_e max rel err {err:.3e}")
+            ex = list(range(e)) if ffn_experts is None else list(ffn_experts)
+            Xe_ref = ref.expert_ffn(Xin_h[ex], inp["W1"][ex], inp["W2"][ex], w.act)
+            err = max_rel_err(Xe_h[ex], Xe_ref)
+            _p(f"[{w.name}] X_e max rel err {err:.3e} (experts checked: {len(ex)} of {e})")
             assert err <= out_tol(w)
     else:
         Xe, Xe_h = Xin, Xin_h
@@ -122,12 +128,25 @@ def _stagewise(m, ref, w, inp, check_ffn=True):
     assert (to_host(I2) == I_h).all() and (to_host(S2) == S_h).all()
     assert (to_host(G2).view(np.uint32) == G_h.view(np.uint32)).all()
     assert (to_host(Xout2) == Xout_h).all()                        # same kernels, same order: bit-identical
-    if w.d_ff > 0 and check_ffn:
+    if w.d_ff > 0 and check_ffn and ffn_experts is None:
         # whole layer against the oracle's FFN + combine on the GPU's routing
         full_ref = ref.combine(ref.expert_ffn(Xin_h, inp["W1"], inp["W2"], w.act), G_h, I_h, n)
         err = max_rel_err(Xout_h, full_ref)
         _p(f"[{w.name}] X_out (layer) max rel err {err:.3e}")
         assert err <= out_tol(w)
+    elif w.d_ff > 0 and check_ffn:
+        # whole layer on the tokens routed only to the sampled experts
+        ex = list(ffn_experts)
+        in_sample = np.zeros(e, bool)
+        in_sample[ex] = True
+        other = np.unique(I_h[~in_sample].ravel())
+        toks = np.setdiff1d(np.unique(I_h[in_sample].ravel()), other)
+        if toks.size:
+            Xe_ref = ref.expert_ffn(Xin_h[ex], inp["W1"][ex], inp["W2"][ex], w.act)
+            part = ref.combine(Xe_ref, G_h[ex], I_h[ex], n)[toks]
+            err = max_rel_err(to_f64(Xout_h)[toks], part)
+            _p(f"[{w.name}] X_out (layer, {toks.size} tokens served only by the sampled experts) max rel err {err:.3e}")
+            assert err <= out_tol(w)
     return dict(S=S_h, I=I_h, G=G_h, Xout=Xout_h)
 
 
@@ -156,6 +175,18 @@ def test_reduced_shapes(m, ref, name, kw):
 
 def test_cfg2_full(m, ref):
     w = wl.WORKLOADS["cfg2"]
+    _stagewise(m, ref, w, wl.make_inputs(w))
+
+
+def test_cfg3_full(m, ref):
+    # full size; the float64 FFN oracle runs on 6 of the 64 experts
+    w = wl.WORKLOADS["cfg3"]
+    _stagewise(m, ref, w, wl.make_inputs(w), ffn_experts=[0, 1, 17, 31, 46, 63])
+
+
+def test_cfg5_full_routing_only(m, ref):
+    # full size: 65536 tokens, 256 experts, skewed scores, identity experts
+    w = wl.WORKLOADS["cfg5"]
     _stagewise(m, ref, w, wl.make_inputs(w))
 
 
