@@ -93,65 +93,72 @@ slots_kernel(const int32_t* __restrict__ I, int32_t* __restrict__ slot_cnt, int3
     }
 }
 
-// Exclusive scan of per-token expert counts by one 1024-thread workgroup.  Each round takes
-// SCAN_PER_THREAD * 1024 tokens: token = round base + u*1024 + tid, so loads stay coalesced.
-constexpr int SCAN_PER_THREAD = 8;
-__global__ void __launch_bounds__(1024)
-offsets_kernel(const uint32_t* __restrict__ bitmap, int32_t* __restrict__ offsets, int n, int words) {
-    __shared__ unsigned int wave_tot[SCAN_PER_THREAD][16];
-    __shared__ unsigned int wave_base[SCAN_PER_THREAD][16];
-    __shared__ unsigned int carry_s;
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    unsigned int carry = 0;
-    for (int base = 0; base < n; base += SCAN_PER_THREAD * 1024) {
-        unsigned int c[SCAN_PER_THREAD], incl[SCAN_PER_THREAD];
+// Exclusive scan of per-token expert counts (popcounts of the bitmap rows) in two launches:
+// block_counts_kernel sums the counts of each block's token range; offsets_kernel adds up the
+// totals of the blocks before it (at most 1024 of them, one per thread) and scans its own range.
+// A block owns `tpb` consecutive tokens (a multiple of 1024), walked 1024 at a time so that
+// loads stay coalesced.
+__device__ __forceinline__ unsigned int token_count(const uint32_t* __restrict__ bitmap, int l, int n, int words) {
+    unsigned int v = 0;
+    if (l < n)
+        for (int w = 0; w < words; ++w) v += __popc(bitmap[(size_t)l * words + w]);
+    return v;
+}
+
+__device__ __forceinline__ unsigned int block_sum_1024(unsigned int v, unsigned int* red /*[16]*/) {
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
 #pragma unroll
-        for (int u = 0; u < SCAN_PER_THREAD; ++u) {
-            const int l = base + u * 1024 + tid;
-            unsigned int v = 0;
-            if (l < n)
-                for (int w = 0; w < words; ++w) v += __popc(bitmap[(size_t)l * words + w]);
-            c[u] = v;
-            incl[u] = v;
-        }
+    for (int off = 32; off > 0; off >>= 1) v += __shfl_xor(v, off, kWave);
+    __syncthreads();  // red may still be read from a previous use
+    if (lane == 0) red[wave] = v;
+    __syncthreads();
+    unsigned int total = 0;
+#pragma unroll
+    for (int w = 0; w < 16; ++w) total += red[w];
+    return total;
+}
+
+__global__ void __launch_bounds__(1024)
+block_counts_kernel(const uint32_t* __restrict__ bitmap, uint32_t* __restrict__ block_tot, int n, int words, int tpb) {
+    __shared__ unsigned int red[16];
+    const int beg = blockIdx.x * tpb;
+    unsigned int v = 0;
+    for (int l0 = beg; l0 < beg + tpb && l0 < n; l0 += 1024) v += token_count(bitmap, l0 + threadIdx.x, n, words);
+    const unsigned int total = block_sum_1024(v, red);
+    if (threadIdx.x == 0) block_tot[blockIdx.x] = total;
+}
+
+__global__ void __launch_bounds__(1024)
+offsets_kernel(const uint32_t* __restrict__ bitmap, const uint32_t* __restrict__ block_tot,
+               int32_t* __restrict__ offsets, int n, int words, int tpb) {
+    __shared__ unsigned int red[16];
+    __shared__ unsigned int wave_tot[16];
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    unsigned int carry = block_sum_1024(tid < (int)blockIdx.x ? block_tot[tid] : 0u, red);  // gridDim.x <= 1024
+    const int beg = blockIdx.x * tpb;
+    for (int l0 = beg; l0 < beg + tpb && l0 < n; l0 += 1024) {
+        const int l = l0 + tid;
+        const unsigned int c = token_count(bitmap, l, n, words);
+        unsigned int incl = c;
 #pragma unroll
         for (int off = 1; off < 64; off <<= 1) {
-#pragma unroll
-            for (int u = 0; u < SCAN_PER_THREAD; ++u) {
-                unsigned int o = __shfl_up(incl[u], off, kWave);
-                if (lane >= off) incl[u] += o;
-            }
+            unsigned int o = __shfl_up(incl, off, kWave);
+            if (lane >= off) incl += o;
         }
-        if (lane == 63) {
-#pragma unroll
-            for (int u = 0; u < SCAN_PER_THREAD; ++u) wave_tot[u][wave] = incl[u];
-        }
+        __syncthreads();  // wave_tot of the previous round has been read
+        if (lane == 63) wave_tot[wave] = incl;
         __syncthreads();
-        if (wave == 0) {
-            // 128 wavefront totals in (u, wave) order: two per lane, exclusive scan across the wavefront
-            const int a = 2 * lane, b = 2 * lane + 1;
-            unsigned int ta = wave_tot[a >> 4][a & 15], tb = wave_tot[b >> 4][b & 15];
-            unsigned int pair = ta + tb, in2 = pair;
+        unsigned int before = 0, total = 0;
 #pragma unroll
-            for (int off = 1; off < 64; off <<= 1) {
-                unsigned int o = __shfl_up(in2, off, kWave);
-                if (lane >= off) in2 += o;
-            }
-            const unsigned int ex = in2 - pair;
-            wave_base[a >> 4][a & 15] = ex;
-            wave_base[b >> 4][b & 15] = ex + ta;
-            if (lane == 63) carry_s = in2;
+        for (int w = 0; w < 16; ++w) {
+            unsigned int t = wave_tot[w];
+            before += w < wave ? t : 0u;
+            total += t;
         }
-        __syncthreads();
-#pragma unroll
-        for (int u = 0; u < SCAN_PER_THREAD; ++u) {
-            const int l = base + u * 1024 + tid;
-            if (l < n) offsets[l] = (int32_t)(carry + wave_base[u][wave] + incl[u] - c[u]);
-        }
-        carry += carry_s;
-        __syncthreads();
+        if (l < n) offsets[l] = (int32_t)(carry + before + incl - c);
+        carry += total;
     }
-    if (tid == 0) offsets[n] = (int32_t)carry;
+    if (blockIdx.x == gridDim.x - 1 && tid == 0) offsets[n] = (int32_t)carry;
 }
 
 __global__ void __launch_bounds__(256)
@@ -256,7 +263,14 @@ int launch_combine(const void* Xe, const float* G, const int32_t* I, void* Xout,
     const int32_t* list = ix.slots;
     if (!ix.use_slots) {
         const int words = (int)ceil_div(e, 32);
-        hipLaunchKernelGGL(offsets_kernel, dim3(1), dim3(1024), 0, stream, ix.bitmap, ix.offsets, (int)n, words);
+        // token range of a scan block: 1024 tokens, more only when that would need over 1024 blocks
+        const int tpb = (int)(ceil_div(ceil_div(n, 1024), 1024) * 1024);
+        const unsigned scan_blocks = (unsigned)ceil_div(n, tpb);
+        uint32_t* block_tot = reinterpret_cast<uint32_t*>(ix.slot_cnt);  // [n] words, idle in the CSR form
+        hipLaunchKernelGGL(block_counts_kernel, dim3(scan_blocks), dim3(1024), 0, stream, ix.bitmap, block_tot, (int)n,
+                           words, tpb);
+        hipLaunchKernelGGL(offsets_kernel, dim3(scan_blocks), dim3(1024), 0, stream, ix.bitmap, block_tot, ix.offsets,
+                           (int)n, words, tpb);
         hipLaunchKernelGGL(inverse_index_kernel, dim3(blocks_for(rows)), dim3(256), 0, stream, I, ix.bitmap, ix.offsets,
                            ix.inv, rows, (int)k, words);
         int rc = check_launch();

@@ -69,11 +69,24 @@ topk_tokens_kernel(const float* __restrict__ St, int n, int k, float* __restrict
 
     // ---- 1. stage + min/max ------------------------------------------------
     unsigned int vmin = 0xFFFFFFFFu, vmax = 0u;
-    for (int idx = tid; idx < n; idx += TOPK_THREADS) {
-        unsigned int v = colg[idx];
-        if (STAGED) cols[idx] = v;
-        vmin = v < vmin ? v : vmin;
-        vmax = v > vmax ? v : vmax;
+    const bool vec_ok = (n & 3) == 0;  // rows are 16-byte aligned: four scores per load
+    if (vec_ok) {
+        const uint4* __restrict__ colg4 = reinterpret_cast<const uint4*>(colg);
+#pragma unroll 4
+        for (int q = tid; q < (n >> 2); q += TOPK_THREADS) {
+            const uint4 v = colg4[q];
+            if (STAGED) reinterpret_cast<uint4*>(cols)[q] = v;
+            const unsigned int lo4 = min(min(v.x, v.y), min(v.z, v.w)), hi4 = max(max(v.x, v.y), max(v.z, v.w));
+            vmin = lo4 < vmin ? lo4 : vmin;
+            vmax = hi4 > vmax ? hi4 : vmax;
+        }
+    } else {
+        for (int idx = tid; idx < n; idx += TOPK_THREADS) {
+            unsigned int v = colg[idx];
+            if (STAGED) cols[idx] = v;
+            vmin = v < vmin ? v : vmin;
+            vmax = v > vmax ? v : vmax;
+        }
     }
 #pragma unroll
     for (int off = 32; off > 0; off >>= 1) {
@@ -103,9 +116,21 @@ topk_tokens_kernel(const float* __restrict__ St, int n, int k, float* __restrict
         const unsigned int hmask = lo >= 32 ? 0u : ~((1u << lo) - 1u);
         if (tid < 256) sh.hist[tid] = 0;
         __syncthreads();
-        for (int idx = tid; idx < n; idx += TOPK_THREADS) {
-            unsigned int key = ld(idx) - vmin;
-            if ((key & hmask) == prefix) atomicAdd(&sh.hist[(key >> nlo) & dmask], 1u);
+        if (!STAGED && vec_ok) {
+            const uint4* __restrict__ colg4 = reinterpret_cast<const uint4*>(colg);
+#pragma unroll 4
+            for (int q = tid; q < (n >> 2); q += TOPK_THREADS) {
+                const uint4 v = colg4[q];
+                const unsigned int k4[4] = {v.x - vmin, v.y - vmin, v.z - vmin, v.w - vmin};
+#pragma unroll
+                for (int u = 0; u < 4; ++u)
+                    if ((k4[u] & hmask) == prefix) atomicAdd(&sh.hist[(k4[u] >> nlo) & dmask], 1u);
+            }
+        } else {
+            for (int idx = tid; idx < n; idx += TOPK_THREADS) {
+                unsigned int key = ld(idx) - vmin;
+                if ((key & hmask) == prefix) atomicAdd(&sh.hist[(key >> nlo) & dmask], 1u);
+            }
         }
         __syncthreads();
         if (wave == 0) {
