@@ -28,9 +28,10 @@ if ROOT not in sys.path:
 PEAK_HBM_GBS = 8000.0          # MI355X HBM3E, published
 PEAK_BF16_TFLOPS = 2500.0      # MI355X dense bf16 MFMA, published
 
-# HBM bytes per expert-FFN call (both products) from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE,
-# see profiles/; None until measured for the workload.
-MEASURED_FFN_TRAFFIC_BYTES = {}
+# HBM bytes per expert-GEMM launch (mean of the two launches of one FFN call) from the rocprofv3
+# --pmc FETCH_SIZE / WRITE_SIZE runs summarised in profiles/cfg2_forward_hbm_traffic.txt
+# (first product 125.48 MiB read + 96.00 MiB written, second 172.61 + 24.38); None where not measured.
+MEASURED_FFN_TRAFFIC_BYTES = {"cfg2": int((125.48 + 96.00 + 172.61 + 24.38) * 1048576 / 2)}
 
 
 def parse_args():
