@@ -69,7 +69,7 @@ size_t ec_moe_workspace_bytes(int64_t n, int64_t d, int64_t e, int64_t k, int64_
  *   Z[l,:] (max-subtracted, fp32).
  * X [n,d] and Wg [d,e] in `dtype`.  S [n,e] and St [e,n] (the transpose, the
  * layout ec_moe_topk_tokens reads) are float outputs; either may be NULL but
- * not both.  e <= EC_MOE_MAX_EXPERTS. */
+ * not both.  e <= EC_MOE_MAX_EXPERTS.  ws is not used (NULL, 0 allowed). */
 int ec_moe_gate(const void* X, const void* Wg, float* S, float* St,
                 int64_t n, int64_t d, int64_t e, int dtype,
                 void* ws, size_t ws_bytes, void* stream);
@@ -78,9 +78,10 @@ int ec_moe_gate(const void* X, const void* Wg, float* S, float* St,
  * largest scores over the n tokens.  St [e,n] float, all values >= 0 (softmax
  * output; negative or NaN values are outside the contract).
  * I [e,k] int32: token indices; G [e,k] float: G[i,j] = St[i, I[i,j]] bit for bit.
- * A bucket is ordered by descending score; equal scores by ascending token
- * index; the same rule decides which of several equal scores are admitted at
- * the k-th place.  The result is therefore unique.  1 <= k <= n. */
+ * Of several equal scores at the k-th place the lower token indices are
+ * admitted.  The paper leaves the order inside a bucket open; here a bucket
+ * lists its tokens by ascending token index, so the result is unique.
+ * 1 <= k <= n.  ws is not used (NULL, 0 allowed). */
 int ec_moe_topk_tokens(const float* St, int64_t n, int64_t e, int64_t k,
                        float* G, int32_t* I, void* ws, size_t ws_bytes, void* stream);
 

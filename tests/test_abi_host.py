@@ -1,0 +1,95 @@
+"""Host-side checks of the C ABI: the library loads, exports every symbol the header declares,
+and rejects bad arguments before anything reaches a GPU (no compute calls here)."""
+import ctypes
+import os
+import re
+
+import pytest
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+@pytest.fixture(scope="module")
+def m():
+    import paper_2202_09368_amd as mod
+    if not os.path.exists(mod.lib_path()):
+        import __graft_entry__
+        __graft_entry__.build()
+    mod.lib()
+    return mod
+
+
+def _declared_functions():
+    text = open(os.path.join(ROOT, "include", "ec_moe.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(ec_moe_\w+)\s*\(", text)))
+
+
+def test_every_declared_symbol_is_exported(m):
+    names = _declared_functions()
+    assert {"ec_moe_gate", "ec_moe_topk_tokens", "ec_moe_dispatch", "ec_moe_expert_ffn", "ec_moe_combine",
+            "ec_moe_forward", "ec_moe_backward", "ec_moe_capacity", "ec_moe_workspace_bytes"} <= set(names)
+    raw = ctypes.CDLL(m.lib_path())
+    for name in names:
+        assert hasattr(raw, name), f"{name} declared in ec_moe.h but not exported"
+
+
+def test_capacity_and_status_strings(m):
+    assert m.ec_moe_capacity(8192, 16, 2.0) == 1024
+    assert m.ec_moe_capacity(65536, 256, 1.0) == 256
+    assert m.ec_moe_capacity(10, 3, 0.5) == 1
+    for bad in [(0, 4, 1.0), (16, 0, 1.0), (16, 4, 0.0), (4, 16, 0.5), (4, 2, 8.0), (4, 2, float("nan"))]:
+        with pytest.raises(m.EcMoeError) as ei:
+            m.ec_moe_capacity(*bad)
+        assert ei.value.status == -1
+    assert m.ec_moe_status_string(0) == "EC_OK"
+    assert m.ec_moe_status_string(-2) == "EC_ERR_WORKSPACE"
+    assert m.ec_moe_status_string(-4) == "EC_ERR_UNSUPPORTED"
+    assert re.match(r"\d+\.\d+", m.ec_moe_version())
+
+
+def test_workspace_sizes(m):
+    small = m.ec_moe_workspace_bytes(256, 64, 8, 64, 256, m.EC_F32)
+    big = m.ec_moe_workspace_bytes(8192, 768, 16, 1024, 3072, m.EC_BF16)
+    assert 0 < small < big and big % 256 == 0
+    assert big >= 16 * 1024 * 3072 * 2           # at least the hidden activations
+    assert m.ec_moe_workspace_bytes(0, 64, 8, 64, 256, m.EC_F32) == 0
+    assert m.ec_moe_workspace_bytes(256, 64, 8, 512, 256, m.EC_F32) == 0      # k > n
+    assert m.ec_moe_workspace_bytes(256, 64, 8, 64, 256, 7) == 0             # unknown dtype
+    assert m.ec_moe_workspace_bytes(256, 64, 2000, 1, 256, m.EC_F32) == 0    # too many experts
+
+
+def test_invalid_arguments_are_rejected_on_the_host(m):
+    lib = m.lib()
+    P = 0x1000   # non-null, 16- and 256-byte aligned; never dereferenced: validation fails first
+    INV, WS = -1, -2
+    # gate: null X, bad dtype, both outputs null, misaligned pointer
+    assert lib.ec_moe_gate(None, P, P, P, 8, 8, 4, 0, None, 0, None) == INV
+    assert lib.ec_moe_gate(P, P, P, P, 8, 8, 4, 9, None, 0, None) == INV
+    assert lib.ec_moe_gate(P, P, None, None, 8, 8, 4, 0, None, 0, None) == INV
+    assert lib.ec_moe_gate(P + 4, P, P, P, 8, 8, 4, 0, None, 0, None) == INV
+    assert lib.ec_moe_gate(P, P, P, P, 8, 8, 5000, 0, None, 0, None) == INV
+    # top-k: k outside [1, n]
+    assert lib.ec_moe_topk_tokens(P, 8, 2, 0, P, P, None, 0, None) == INV
+    assert lib.ec_moe_topk_tokens(P, 8, 2, 9, P, P, None, 0, None) == INV
+    assert lib.ec_moe_topk_tokens(None, 8, 2, 4, P, P, None, 0, None) == INV
+    # dispatch: bf16 rows must be multiples of 8 elements
+    assert lib.ec_moe_dispatch(P, P, P, 8, 12, 2, 4, 1, None) == INV
+    assert lib.ec_moe_dispatch(P, None, P, 8, 16, 2, 4, 1, None) == INV
+    # expert FFN: bad activation, missing workspace for the hidden buffer
+    assert lib.ec_moe_expert_ffn(P, P, P, P, None, None, 2, 4, 16, 32, 5, 1, P, 1 << 20, None) == INV
+    assert lib.ec_moe_expert_ffn(P, P, P, P, None, None, 2, 4, 16, 32, 1, 1, None, 0, None) == WS
+    assert lib.ec_moe_expert_ffn(P, P, P, P, None, None, 2, 4, 16, 32, 1, 1, P, 16, None) == WS
+    # combine: workspace too small / misaligned
+    assert lib.ec_moe_combine(P, P, P, P, 8, 16, 2, 4, 1, P, 8, None) == WS
+    assert lib.ec_moe_combine(P, P, P, P, 8, 16, 2, 4, 1, P + 16, 1 << 20, None) == WS
+    assert lib.ec_moe_combine(P, P, None, P, 8, 16, 2, 4, 1, P, 1 << 20, None) == INV
+    # forward: capacity outside [1, n]; identity experts need the identity activation; one weight missing
+    fwd = lambda W1, W2, c, act, ws, wsb: lib.ec_moe_forward(P, P, W1, W2, c, P, None, None, None, None, None,
+                                                             None, None, 64, 16, 4, 32, act, 1, ws, wsb, None)
+    assert fwd(P, P, 0.001, 1, P, 1 << 30) == INV
+    assert fwd(None, None, 2.0, 1, P, 1 << 30) == INV
+    assert fwd(P, None, 2.0, 1, P, 1 << 30) == INV
+    assert fwd(P, P, 2.0, 1, None, 0) == WS
+    assert fwd(P, P, 2.0, 1, P, 64) == WS
+    assert m.ec_moe_last_hip_error() == 0      # nothing was launched
