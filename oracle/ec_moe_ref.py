@@ -204,44 +204,67 @@ def forward(X, Wg, W1, W2, c: float, act: int) -> Dict[str, np.ndarray]:
 
 
 # ---------------------------------------------------------------- backward ---
-def backward(X, Wg, W1, W2, act: int, S: np.ndarray, G: np.ndarray, I: np.ndarray,
-             dY: np.ndarray) -> Dict[str, np.ndarray]:
-    """Gradients of L = <dY, X_out> w.r.t. X, Wg, W1, W2 (derived from Eq. 2-4).
-
-    The selection I is a constant.  The gate values G[i,j] = S[I[i,j], i] are
-    differentiable, so W_g and X also receive gradient through the softmax.
-    S, G, I are the forward's routing tensors (float32 / int32), taken as
-    given so that the same selection is differentiated on both sides.
-    """
-    Xd, Wgd, dYd = widen(X), widen(Wg), widen(dY)
-    Sd, Gd = widen(S), widen(G)
-    n, d = Xd.shape
-    e, k = I.shape
+# The paper prints no backward pass.  These are the derivatives of Eq. 4, Eq. 3 and Eq. 2 in that
+# order, with the selection I a constant and the gate values G[i,j] = S[I[i,j], i] differentiable.
+def backward_combine(dY, X_e, G, I) -> Tuple[np.ndarray, np.ndarray]:
+    """Eq. 4 differentiated: dX_e[i,j,:] = G[i,j] dY[I[i,j],:] and dG[i,j] = <dY[I[i,j],:], X_e[i,j,:]>."""
+    dYd, Xed, Gd = widen(dY), widen(X_e), widen(G)
     Ii = np.asarray(I, dtype=np.int64)
+    dYsel = dYd[Ii, :]                                         # [e,k,d] rows of dY each bucket row fed
+    dXe = Gd[:, :, None] * dYsel
+    dG = np.einsum("ijt,ijt->ij", dYsel, Xed)
+    return dXe, dG
 
-    X_in = Xd[Ii, :]                                            # [e,k,d]
-    dS = np.zeros((n, e), dtype=np.float64)
-    dX = np.zeros((n, d), dtype=np.float64)
+
+def backward_ffn(X_in, W1, W2, act: int, dXe) -> Tuple[np.ndarray, np.ndarray, np.ndarray]:
+    """Eq. 3 differentiated, expert by expert: returns dX_in [e,k,d], dW1 [e,d,d_ff], dW2 [e,d_ff,d]."""
+    X_in = widen(X_in)
+    e = X_in.shape[0]
+    dXin = np.empty_like(X_in)
     dW1 = np.empty(np.asarray(W1).shape, dtype=np.float64)
     dW2 = np.empty(np.asarray(W2).shape, dtype=np.float64)
     for i in range(e):
         W1i, W2i = widen(W1[i]), widen(W2[i])
         A = X_in[i] @ W1i                                       # [k,d_ff]
         H = activation(A, act)
-        X_e = H @ W2i                                           # [k,d]
-        dYsel = dYd[Ii[i], :]                                   # rows of dY this expert fed
-        dXe = Gd[i][:, None] * dYsel                            # dL/dX_e
-        dG = np.einsum("jt,jt->j", dYsel, X_e)                  # dL/dG[i,:]
-        dW2[i] = H.T @ dXe
-        dH = dXe @ W2i.T
+        dW2[i] = H.T @ dXe[i]
+        dH = dXe[i] @ W2i.T
         dA = dH * activation_grad(A, act)
         dW1[i] = X_in[i].T @ dA
-        dXin = dA @ W1i.T                                       # [k,d]
-        for j in range(k):                                      # each token at most once per expert
-            dX[Ii[i, j], :] += dXin[j, :]
-            dS[Ii[i, j], i] = dG[j]
-    # softmax backward, row by row: dZ = S * (dS - <dS, S>)
+        dXin[i] = dA @ W1i.T
+    return dXin, dW1, dW2
+
+
+def backward_gate(X, Wg, S, dG, I) -> Tuple[np.ndarray, np.ndarray, np.ndarray]:
+    """Eq. 2 differentiated: dS is dG scattered to the selected (token, expert) pairs, the softmax
+    backward gives dZ = S * (dS - <dS, S>) row by row, then dWg = X^T dZ and the gate's share of dX."""
+    Xd, Wgd, Sd = widen(X), widen(Wg), widen(S)
+    n = Xd.shape[0]
+    e, k = np.asarray(I).shape
+    Ii = np.asarray(I, dtype=np.int64)
+    dS = np.zeros((n, e), dtype=np.float64)
+    for i in range(e):
+        dS[Ii[i], i] = dG[i]                                    # each token at most once per expert
     dZ = Sd * (dS - (dS * Sd).sum(axis=1, keepdims=True))
-    dWg = Xd.T @ dZ
-    dX += dZ @ Wgd.T
-    return {"dX": dX, "dWg": dWg, "dW1": dW1, "dW2": dW2, "dS": dS, "dZ": dZ}
+    return Xd.T @ dZ, dZ @ Wgd.T, dZ
+
+
+def backward(X, Wg, W1, W2, act: int, S: np.ndarray, G: np.ndarray, I: np.ndarray,
+             dY: np.ndarray) -> Dict[str, np.ndarray]:
+    """Gradients of L = <dY, X_out> w.r.t. X, Wg, W1, W2 (derived from Eq. 2-4).
+
+    S, G, I are the forward's routing tensors (float32 / int32), taken as given so that the same
+    selection is differentiated on both sides.
+    """
+    Ii = np.asarray(I, dtype=np.int64)
+    n, d = np.asarray(X).shape
+    e, k = Ii.shape
+    X_in = widen(X)[Ii, :]
+    X_e = expert_ffn(X_in, W1, W2, act)
+    dXe, dG = backward_combine(dY, X_e, G, I)
+    dXin, dW1, dW2 = backward_ffn(X_in, W1, W2, act, dXe)
+    dWg, dX, dZ = backward_gate(X, Wg, S, dG, I)
+    for i in range(e):
+        for j in range(k):                                      # Eq. 3 gather differentiated: scatter-add
+            dX[Ii[i, j], :] += dXin[i, j, :]
+    return {"dX": dX, "dWg": dWg, "dW1": dW1, "dW2": dW2, "dZ": dZ, "dG": dG}

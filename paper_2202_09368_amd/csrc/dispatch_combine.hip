@@ -183,7 +183,8 @@ inverse_index_kernel(const int32_t* __restrict__ I, const uint32_t* __restrict__
 template <typename T, int VEC, int CAP>
 __global__ void __launch_bounds__(256)
 combine_kernel(const T* __restrict__ Xe, const float* __restrict__ G, const int32_t* __restrict__ offsets,
-               const int32_t* __restrict__ inv, T* __restrict__ Xout, int n, int d, int tpr) {
+               const int32_t* __restrict__ inv, T* __restrict__ Xout, int n, int d, int tpr,
+               const float* __restrict__ addend) {
     typedef T vec_t __attribute__((ext_vector_type(VEC)));
     constexpr int NRAW = CAP > 0 ? CAP : 1;
     const int tok_per_block = 256 / tpr;
@@ -204,7 +205,7 @@ combine_kernel(const T* __restrict__ Xe, const float* __restrict__ G, const int3
         for (int v = t; v < vec_per_row; v += tpr) {
             float acc[VEC];
 #pragma unroll
-            for (int q = 0; q < VEC; ++q) acc[q] = 0.0f;
+            for (int q = 0; q < VEC; ++q) acc[q] = addend != nullptr ? addend[(size_t)l * d + (size_t)v * VEC + q] : 0.0f;
             int last = -1;
             for (int p = 0; p < cnt; ++p) {
                 int r;
@@ -217,7 +218,7 @@ combine_kernel(const T* __restrict__ Xe, const float* __restrict__ G, const int3
                 } else {
                     r = inv[beg + p];
                 }
-                const float g = G[r];
+                const float g = G != nullptr ? G[r] : 1.0f;  // no weights: plain scatter-add of rows
                 vec_t x = *reinterpret_cast<const vec_t*>(Xe + (size_t)r * d + (size_t)v * VEC);
 #pragma unroll
                 for (int q = 0; q < VEC; ++q) acc[q] = fmaf(g, Cvt<T>::to_f32(x[q]), acc[q]);
@@ -255,26 +256,35 @@ int launch_combine_index(const int32_t* I, int64_t n, int64_t e, int64_t k, cons
     return check_launch();
 }
 
-// Applies Eq. 4 given a filled index (slot lists, or the bitmap from which the CSR lists are finished here).
-int launch_combine(const void* Xe, const float* G, const int32_t* I, void* Xout, int64_t n, int64_t d,
-                   int64_t e, int64_t k, int dtype, const CombineIndex& ix, hipStream_t stream) {
+// Finishes the CSR form from a filled bitmap: offsets (exclusive scan) and the expert-ascending row lists.
+int launch_combine_csr(const int32_t* I, int64_t n, int64_t e, int64_t k, const CombineIndex& ix, hipStream_t stream) {
     const long long rows = (long long)e * k;
+    const int words = (int)ceil_div(e, 32);
+    // token range of a scan block: 1024 tokens, more only when that would need over 1024 blocks
+    const int tpb = (int)(ceil_div(ceil_div(n, 1024), 1024) * 1024);
+    const unsigned scan_blocks = (unsigned)ceil_div(n, tpb);
+    uint32_t* block_tot = reinterpret_cast<uint32_t*>(ix.slot_cnt);  // [n] words, idle in the CSR form
+    hipLaunchKernelGGL(block_counts_kernel, dim3(scan_blocks), dim3(1024), 0, stream, ix.bitmap, block_tot, (int)n,
+                       words, tpb);
+    hipLaunchKernelGGL(offsets_kernel, dim3(scan_blocks), dim3(1024), 0, stream, ix.bitmap, block_tot, ix.offsets,
+                       (int)n, words, tpb);
+    hipLaunchKernelGGL(inverse_index_kernel, dim3(blocks_for(rows)), dim3(256), 0, stream, I, ix.bitmap, ix.offsets,
+                       ix.inv, rows, (int)k, words);
+    return check_launch();
+}
+
+// Applies Eq. 4 given a filled index (slot lists, or the bitmap from which the CSR lists are finished here).
+// G == nullptr adds the rows unweighted; `addend` (fp32 [n,d], optional) is the starting value of every row.
+int launch_combine(const void* Xe, const float* G, const int32_t* I, void* Xout, int64_t n, int64_t d,
+                   int64_t e, int64_t k, int dtype, const CombineIndex& ix, hipStream_t stream,
+                   const float* addend, bool csr_ready) {
     const int32_t* offs = ix.slot_cnt;
     const int32_t* list = ix.slots;
     if (!ix.use_slots) {
-        const int words = (int)ceil_div(e, 32);
-        // token range of a scan block: 1024 tokens, more only when that would need over 1024 blocks
-        const int tpb = (int)(ceil_div(ceil_div(n, 1024), 1024) * 1024);
-        const unsigned scan_blocks = (unsigned)ceil_div(n, tpb);
-        uint32_t* block_tot = reinterpret_cast<uint32_t*>(ix.slot_cnt);  // [n] words, idle in the CSR form
-        hipLaunchKernelGGL(block_counts_kernel, dim3(scan_blocks), dim3(1024), 0, stream, ix.bitmap, block_tot, (int)n,
-                           words, tpb);
-        hipLaunchKernelGGL(offsets_kernel, dim3(scan_blocks), dim3(1024), 0, stream, ix.bitmap, block_tot, ix.offsets,
-                           (int)n, words, tpb);
-        hipLaunchKernelGGL(inverse_index_kernel, dim3(blocks_for(rows)), dim3(256), 0, stream, I, ix.bitmap, ix.offsets,
-                           ix.inv, rows, (int)k, words);
-        int rc = check_launch();
-        if (rc != EC_OK) return rc;
+        if (!csr_ready) {
+            int rc = launch_combine_csr(I, n, e, k, ix, stream);
+            if (rc != EC_OK) return rc;
+        }
         offs = ix.offsets;
         list = ix.inv;
     }
@@ -286,16 +296,16 @@ int launch_combine(const void* Xe, const float* G, const int32_t* I, void* Xout,
         dim3 grid((unsigned)blocks), block(256);                                                              \
         if (!ix.use_slots)                                                                                    \
             hipLaunchKernelGGL((combine_kernel<TYPE, VECV, 0>), grid, block, 0, stream, (const TYPE*)Xe, G,   \
-                               offs, list, (TYPE*)Xout, (int)n, (int)d, tpr);                                 \
+                               offs, list, (TYPE*)Xout, (int)n, (int)d, tpr, addend);                                 \
         else if (ix.slot_cap == 4)                                                                            \
             hipLaunchKernelGGL((combine_kernel<TYPE, VECV, 4>), grid, block, 0, stream, (const TYPE*)Xe, G,   \
-                               offs, list, (TYPE*)Xout, (int)n, (int)d, tpr);                                 \
+                               offs, list, (TYPE*)Xout, (int)n, (int)d, tpr, addend);                                 \
         else if (ix.slot_cap == 8)                                                                            \
             hipLaunchKernelGGL((combine_kernel<TYPE, VECV, 8>), grid, block, 0, stream, (const TYPE*)Xe, G,   \
-                               offs, list, (TYPE*)Xout, (int)n, (int)d, tpr);                                 \
+                               offs, list, (TYPE*)Xout, (int)n, (int)d, tpr, addend);                                 \
         else                                                                                                  \
             hipLaunchKernelGGL((combine_kernel<TYPE, VECV, 16>), grid, block, 0, stream, (const TYPE*)Xe, G,  \
-                               offs, list, (TYPE*)Xout, (int)n, (int)d, tpr);                                 \
+                               offs, list, (TYPE*)Xout, (int)n, (int)d, tpr, addend);                                 \
     } while (0)
     if (dtype == EC_BF16) EC_COMBINE_LAUNCH(bf16_t, 8, d / 8);
     else if (d % 4 == 0) EC_COMBINE_LAUNCH(float, 4, d / 4);

@@ -98,8 +98,10 @@ bool ffn_can_gather(int dtype, int64_t n, int64_t k, int64_t d, int64_t d_ff);
 int launch_ffn(const void* Xin, const void* X, const int32_t* I, int64_t n, const void* W1, const void* W2, void* Xe,
                void* A_save, void* H, int64_t e, int64_t k, int64_t d, int64_t d_ff, int act, int dtype,
                hipStream_t stream);
+int launch_combine_csr(const int32_t* I, int64_t n, int64_t e, int64_t k, const CombineIndex& ix, hipStream_t stream);
 int launch_combine(const void* Xe, const float* G, const int32_t* I, void* Xout, int64_t n, int64_t d,
-                   int64_t e, int64_t k, int dtype, const CombineIndex& ix, hipStream_t stream);
+                   int64_t e, int64_t k, int dtype, const CombineIndex& ix, hipStream_t stream,
+                   const float* addend = nullptr, bool csr_ready = false);
 int launch_backward(const void* dY, const void* X, const void* Wg, const void* W1, const void* W2,
                     const float* S, const float* G, const int32_t* I, const void* Xin, const void* A,
                     const void* H, const void* Xe, void* dX, float* dWg, float* dW1, float* dW2,

@@ -1,6 +1,6 @@
 // Grouped bf16 GEMM on the matrix cores, shared by the forward expert FFN and the backward pass:
 //   C[g] = epilogue( opA(A[g]) . opB(B[g]) ),   M x K times K x N, fp32 accumulation,
-// one launch for all groups g (experts).  K must be a multiple of 64.
+// one launch for all groups g (experts).
 //
 // Operand storage (template flags):
 //   A_MC = false  A[g] is [M][K]  (contraction-contiguous rows)
@@ -273,7 +273,7 @@ gemm_bf16_kernel(const bf16_t* __restrict__ Aall, const bf16_t* __restrict__ Bal
     };
 
     // Loads past the last stage read zeros or in-range data of the same group: harmless, never consumed.
-    const int nk = K / GEMM_BK;
+    const int nk = (K + GEMM_BK - 1) / GEMM_BK;  // a ragged K is legal only when both operands keep k as the row index
     load_tiles(0);
     if (STAGES == 2) {
         store_tiles(0);
@@ -415,10 +415,13 @@ constexpr size_t gemm_bf16_lds_bytes() {
            sizeof(bf16_t);
 }
 
-// True when the fast kernel covers the shape (otherwise callers fall back or refuse).
-inline bool gemm_bf16_shape_ok(int64_t M, int64_t N, int64_t K) {
-    return (K % GEMM_BK) == 0 && (N % 8) == 0 && M * K * 2 < ((int64_t)1 << 31) && K * N * 2 < ((int64_t)1 << 31) &&
-           M * N < ((int64_t)1 << 31);
+// True when the kernel covers the shape (otherwise callers fall back or refuse).  A contraction-
+// contiguous operand needs K % 64 == 0 (the tail of a row would run into the next row); operands that
+// keep k as the row index are zero-filled past K by the buffer range check.
+inline bool gemm_bf16_shape_ok(int64_t M, int64_t N, int64_t K, bool k_contiguous_operand = true,
+                               bool m_contiguous_operand = false) {
+    return (!k_contiguous_operand || (K % GEMM_BK) == 0) && (N % 8) == 0 && (!m_contiguous_operand || (M % 8) == 0) &&
+           M * K * 2 < ((int64_t)1 << 31) && K * N * 2 < ((int64_t)1 << 31) && M * N < ((int64_t)1 << 31);
 }
 
 template <int BM, int BN, int STAGES, int OCC, bool A_MC, bool B_KC, int EPI, int ACT>
