@@ -5,7 +5,10 @@ import pytest
 import torch
 
 import workloads as wl
-from gpu_util import max_rel_err, to_dev, to_host, torch_dtype
+import os
+import time
+
+from gpu_util import max_rel_err, max_rel_err_rows, score_tolerance, to_dev, to_f64, to_host, torch_dtype
 
 pytestmark = pytest.mark.gpu
 
@@ -25,7 +28,7 @@ def ref():
     return ec_moe_ref
 
 
-def _forward_backward(m, w, inp):
+def _forward_backward(m, w, inp, keep_on_device=False):
     n, d, e, k, f = w.n, w.d, w.e, w.k, w.d_ff
     dt = torch_dtype(w)
     t = {key: to_dev(inp[key]) for key in ("X", "Wg", "W1", "W2", "dY")}
@@ -47,6 +50,8 @@ def _forward_backward(m, w, inp):
     dW2 = torch.full((e, f, d), float("nan"), dtype=torch.float32, **dev)
     m.ec_moe_backward(t["dY"], t["X"], t["Wg"], t["W1"], t["W2"], S, G, I, Xin, A, H, Xe, dX, dWg, dW1, dW2, w.act, ws)
     torch.cuda.synchronize()
+    if keep_on_device:
+        return dict(S=S, G=G, I=I, dX=dX, dWg=dWg, dW1=dW1, dW2=dW2, Xe=Xe, Xout=Xout)
     return dict(S=to_host(S), G=to_host(G), I=to_host(I), dX=to_host(dX), dWg=to_host(dWg), dW1=to_host(dW1),
                 dW2=to_host(dW2))
 
@@ -71,3 +76,72 @@ def test_backward_reduced(m, ref, name, kw, tol):
         print(f"[bwd {w.name}] {key} max rel err {err:.3e}", flush=True)
         errs[key] = err
     assert all(v <= (1.5 * tol if key == "dX" else tol) for key, v in errs.items()), errs
+
+
+def _progress(msg):
+    """Progress of the long full-size test, to stdout and to a file a watcher can see grow."""
+    line = f"[cfg4 {time.strftime('%H:%M:%S')}] {msg}"
+    print(line, flush=True)
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    try:
+        os.makedirs(os.path.join(root, "gpurun_out"), exist_ok=True)
+        with open(os.path.join(root, "gpurun_out", "cfg4_full_progress.log"), "a") as f:
+            f.write(line + "\n")
+    except OSError:
+        pass
+
+
+def test_cfg4_full_forward_backward(m, ref):
+    """Full size: 32768 tokens, d=2048, 128 experts, d_ff=8192, forward + backward.  The float64 oracle
+    runs the expert FFN (forward and backward) on a sample of experts; the gate gradient is checked
+    with the oracle's Eq. 4 / Eq. 2 derivatives fed with the GPU's X_e (itself checked on the sample)."""
+    w = wl.WORKLOADS["cfg4"]
+    n, d, e, k = w.n, w.d, w.e, w.k
+    _progress("drawing inputs")
+    inp = wl.make_inputs(w)
+    _progress("forward + backward on the GPU")
+    r = _forward_backward(m, w, inp, keep_on_device=True)
+    S, G, I = to_host(r["S"]), to_host(r["G"]), to_host(r["I"])
+
+    _progress("scores and selection")
+    S_ref = ref.gate(inp["X"], inp["Wg"])
+    assert (max_rel_err_rows(S, S_ref) <= score_tolerance(inp["X"], inp["Wg"])).all()
+    G_o, I_o = ref.topk_tokens(S, k)
+    assert (I_o == I).all() and (G_o.view(np.uint32) == G.view(np.uint32)).all()
+
+    ex = [0, 77, 127]
+    _progress(f"oracle FFN forward/backward on experts {ex}")
+    Xin_ex = ref.dispatch(inp["X"], I[ex])
+    Xe_ref = ref.expert_ffn(Xin_ex, inp["W1"][ex], inp["W2"][ex], w.act)
+    Xe_gpu = to_host(r["Xe"])
+    err = max_rel_err(Xe_gpu[ex], Xe_ref)
+    _progress(f"X_e max rel err {err:.3e}")
+    assert err <= 2e-2
+    dXe_ref, _ = ref.backward_combine(inp["dY"], Xe_ref, G[ex], I[ex])
+    dXin_ref, dW1_ref, dW2_ref = ref.backward_ffn(Xin_ex, inp["W1"][ex], inp["W2"][ex], w.act, dXe_ref)
+    idx = torch.tensor(ex, device="cuda")
+    for key, want in (("dW1", dW1_ref), ("dW2", dW2_ref)):
+        err = max_rel_err(to_host(r[key].index_select(0, idx)), want)
+        _progress(f"{key}[sample] max rel err {err:.3e}")
+        assert err <= 2e-2, key
+
+    _progress("gate gradient (Eq. 4 and Eq. 2 derivatives on the GPU's X_e)")
+    _, dG_t = ref.backward_combine(inp["dY"], Xe_gpu, G, I)
+    dWg_ref, dXgate, _ = ref.backward_gate(inp["X"], inp["Wg"], S, dG_t, I)
+    err = max_rel_err(to_host(r["dWg"]), dWg_ref)
+    _progress(f"dWg max rel err {err:.3e}")
+    assert err <= 2e-2
+
+    # dX on the tokens that only the sampled experts selected
+    in_sample = np.zeros(e, bool)
+    in_sample[ex] = True
+    other = np.unique(I[~in_sample].ravel())
+    toks = np.setdiff1d(np.unique(I[in_sample].ravel()), other)
+    assert toks.size > 0
+    dX_ref = dXgate.copy()
+    for a, i in enumerate(ex):
+        for j in range(k):
+            dX_ref[I[i, j], :] += dXin_ref[a, j, :]
+    err = max_rel_err(to_f64(to_host(r["dX"]))[toks], dX_ref[toks])
+    _progress(f"dX on {toks.size} tokens served only by the sample: max rel err {err:.3e}")
+    assert err <= 3e-2

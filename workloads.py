@@ -91,6 +91,23 @@ def _normal(rng: np.random.Generator, shape, std: float) -> np.ndarray:
     return out
 
 
+_CHUNKED_ABOVE = 1 << 28  # elements; larger tensors are drawn slice by slice along the first axis
+
+
+def _normal_stored(rng: np.random.Generator, shape, std: float, bf16: bool) -> np.ndarray:
+    """Like _normal, then the storage conversion.  Very large tensors (the 128-expert weights) are drawn
+    one leading slice at a time from the same stream, which keeps the temporaries small."""
+    count = int(np.prod(shape))
+    if count <= _CHUNKED_ABOVE:
+        a = _normal(rng, shape, std)
+        return f32_to_bf16_bits(a) if bf16 else a
+    out = np.empty(shape, dtype=np.uint16 if bf16 else np.float32)
+    for i in range(shape[0]):
+        a = _normal(rng, shape[1:], std)
+        out[i] = f32_to_bf16_bits(a) if bf16 else a
+    return out
+
+
 def make_inputs(w: Workload, with_dy: Optional[bool] = None) -> Dict[str, np.ndarray]:
     """Draw X, Wg, W1, W2 (and dY for backward workloads) for a workload.
 
@@ -111,14 +128,15 @@ def make_inputs(w: Workload, with_dy: Optional[bool] = None) -> Dict[str, np.nda
         out["skew_rows"] = np.sort(rows).astype(np.int64)
     out["X"] = X
     out["Wg"] = _normal(np.random.default_rng(s_wg), (w.d, w.e), (1.0 / w.d) ** 0.5)
+    bf16 = w.dtype == DTYPE_BF16
     if w.d_ff > 0:
-        out["W1"] = _normal(np.random.default_rng(s_w1), (w.e, w.d, w.d_ff), (1.0 / w.d) ** 0.5)
-        out["W2"] = _normal(np.random.default_rng(s_w2), (w.e, w.d_ff, w.d), (1.0 / w.d_ff) ** 0.5)
+        out["W1"] = _normal_stored(np.random.default_rng(s_w1), (w.e, w.d, w.d_ff), (1.0 / w.d) ** 0.5, bf16)
+        out["W2"] = _normal_stored(np.random.default_rng(s_w2), (w.e, w.d_ff, w.d), (1.0 / w.d_ff) ** 0.5, bf16)
     if with_dy if with_dy is not None else w.backward:
         out["dY"] = _normal(np.random.default_rng(s_dy), (w.n, w.d), 1.0)
 
-    if w.dtype == DTYPE_BF16:
-        for key in ("X", "Wg", "W1", "W2", "dY"):
+    if bf16:
+        for key in ("X", "Wg", "dY"):
             if key in out:
                 out[key] = f32_to_bf16_bits(out[key])
     return out
