@@ -39,7 +39,8 @@ def parse_args():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=50)
     ap.add_argument("--warmup", type=int, default=10)
-    ap.add_argument("--workload", default="cfg2", help="cfg2 (headline), cfg3, cfg5")
+    ap.add_argument("--workload", default="cfg2",
+                    help="cfg2 (headline), cfg3, cfg5 (routing only), cfg4 (forward + backward)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--copy-calibration", type=int, default=0, metavar="MiB",
                     help="only run a plain device-to-device copy of this many MiB five times (reference "
@@ -94,12 +95,33 @@ def main() -> int:
     K, W = args.steps, args.warmup
 
     # ---- timed region 1: whole layer ----------------------------------------
+    if w.backward:
+        # forward + backward workload: the forward keeps what the backward consumes
+        f32 = torch.float32
+        dY = dev(wl.make_inputs(wl.scaled(w, d_ff=0), with_dy=True)["dY"])
+        ws = m.alloc_workspace(n, d, e, k, d_ff, w.dtype, with_backward=True)
+        sv = dict(S=torch.empty((n, e), dtype=f32, device="cuda"), G=torch.empty((e, k), dtype=f32, device="cuda"),
+                  I=torch.empty((e, k), dtype=torch.int32, device="cuda"),
+                  Xin=torch.empty((e, k, d), dtype=dt, device="cuda"), A=torch.empty((e, k, d_ff), dtype=dt, device="cuda"),
+                  H=torch.empty((e, k, d_ff), dtype=dt, device="cuda"), Xe=torch.empty((e, k, d), dtype=dt, device="cuda"))
+        gr = dict(dX=torch.empty((n, d), dtype=dt, device="cuda"), dWg=torch.empty((d, e), dtype=f32, device="cuda"),
+                  dW1=torch.empty((e, d, d_ff), dtype=f32, device="cuda"),
+                  dW2=torch.empty((e, d_ff, d), dtype=f32, device="cuda"))
+
+        def step():
+            m.ec_moe_forward(X, Wg, W1, W2, w.c, Xout, w.act, ws, S_out=sv["S"], G_out=sv["G"], I_out=sv["I"],
+                             Xin_out=sv["Xin"], A_out=sv["A"], H_out=sv["H"], Xe_out=sv["Xe"])
+            m.ec_moe_backward(dY, X, Wg, W1, W2, sv["S"], sv["G"], sv["I"], sv["Xin"], sv["A"], sv["H"], sv["Xe"],
+                              gr["dX"], gr["dWg"], gr["dW1"], gr["dW2"], w.act, ws)
+    else:
+        def step():
+            m.ec_moe_forward(X, Wg, W1, W2, w.c, Xout, w.act, ws)
     for _ in range(W):
-        m.ec_moe_forward(X, Wg, W1, W2, w.c, Xout, w.act, ws)
+        step()
     torch.cuda.synchronize()
     t0 = time.perf_counter()
     for _ in range(K):
-        m.ec_moe_forward(X, Wg, W1, W2, w.c, Xout, w.act, ws)
+        step()
     torch.cuda.synchronize()
     t1 = time.perf_counter()
     ms_per_step = (t1 - t0) * 1e3 / K
@@ -218,7 +240,8 @@ def main() -> int:
         "n_gpus": 1, "steps": K, "warmup": W, "ms_per_step": round(ms_per_step, 4),
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "bf16" if w.dtype == wl.DTYPE_BF16 else "f32", "data": "synthetic",
-        "config": {"workload": f"{w.name}: EC-MoE layer forward, n={n} d={d} e={e} c={w.c:g} k={k} d_ff={d_ff}",
+        "config": {"workload": f"{w.name}: EC-MoE layer forward{' + backward' if w.backward else ''}, "
+                               f"n={n} d={d} e={e} c={w.c:g} k={k} d_ff={d_ff}",
                    "act": {0: "relu", 1: "gelu", 2: "identity"}[w.act], "seed": w.seed},
         "roofline": roofline, "cpu_baseline": cpu_baseline, "stages": stages,
     }
