@@ -89,7 +89,7 @@ int launch_gate(const void* X, const void* Wg, float* S, float* St, int64_t n, i
                 int dtype, uint32_t* zero_buf, int64_t zero_words, hipStream_t stream);
 int launch_topk(const float* St, int64_t n, int64_t e, int64_t k, float* G, int32_t* I,
                 unsigned long long* sortkeys_ws, int32_t* slot_cnt, int32_t* slots, int slot_cap, uint32_t* bitmap,
-                hipStream_t stream);
+                hipStream_t stream, int64_t groups = 1);
 int launch_combine_index(const int32_t* I, int64_t n, int64_t e, int64_t k, const CombineIndex& ix,
                          hipStream_t stream);
 int launch_dispatch(const void* X, const int32_t* I, void* Xin, int64_t n, int64_t d, int64_t e, int64_t k,

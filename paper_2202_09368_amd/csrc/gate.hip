@@ -7,7 +7,10 @@
 //    (lane and lane^32) and the softmax needs a single cross-lane exchange.
 //    Stores S^T [e,n] with 32 consecutive tokens per store instruction.
 //  * gate_generic_kernel  any dtype / shape; one wavefront per token, plain fp32 FMAs.
+// With more than 64 experts and enough tokens to fill the chip the product runs on the grouped-GEMM
+// kernel instead (gemm_bf16.h, softmax epilogue).
 #include "ec_common.h"
+#include "gemm_bf16.h"
 
 namespace ecmoe {
 
@@ -193,6 +196,22 @@ gate_generic_kernel(const T* __restrict__ X, const T* __restrict__ Wg, float* __
 int launch_gate(const void* X, const void* Wg, float* S, float* St, int64_t n, int64_t d, int64_t e,
                 int dtype, uint32_t* zero_buf, int64_t zero_words, hipStream_t stream) {
     const bool mfma = dtype == EC_BF16 && (d % GATE_BK) == 0 && e <= 256 && (e % 8) == 0;
+    // Many experts and many tokens: X.Wg is a real matrix product.  It runs on the grouped-GEMM kernel
+    // (one group, all experts inside one tile) whose epilogue does the softmax and clears the counters.
+    if (mfma && e > 64 && gemm_bf16_shape_ok(n, e, d)) {
+        if (e > 128 && n >= 128 * 256) {
+            gemm_bf16_launch<256, 256, 2, 1, false, false, EPI_SOFTMAX, EC_ACT_IDENTITY>(
+                (const bf16_t*)X, (const bf16_t*)Wg, St, S, 1, (int)n, (int)e, (int)d,
+                reinterpret_cast<const int32_t*>(zero_buf), (int)zero_words, stream);
+            return check_launch();
+        }
+        if (e <= 128 && n >= 128 * 128) {
+            gemm_bf16_launch<128, 128, 1, 2, false, false, EPI_SOFTMAX, EC_ACT_IDENTITY>(
+                (const bf16_t*)X, (const bf16_t*)Wg, St, S, 1, (int)n, (int)e, (int)d,
+                reinterpret_cast<const int32_t*>(zero_buf), (int)zero_words, stream);
+            return check_launch();
+        }
+    }
     if (mfma) {
         const int et = e <= 32 ? 1 : e <= 64 ? 2 : e <= 128 ? 4 : 8;
         // one wavefront per block while that still leaves blocks for every compute unit, four otherwise

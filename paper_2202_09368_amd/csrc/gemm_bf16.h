@@ -35,7 +35,10 @@ enum GemmEpilogue {
     EPI_ACT = 0,       // C (bf16) = act(acc)
     EPI_ACT_SAVE = 1,  // additionally C2 (bf16) = acc
     EPI_MULGRAD = 2,   // C (bf16) = acc * act'(C2[m][n]),  C2 = bf16 pre-activations (read)
-    EPI_F32 = 3        // C (fp32) = acc
+    EPI_F32 = 3,       // C (fp32) = acc
+    EPI_SOFTMAX = 4    // one group, N <= BN: C (fp32, [N][M]) = softmax over n of acc[m][:], transposed;
+                       // C2 (fp32, [M][N], optional) the same untransposed.  `gather` is not used for
+                       // loads here: it names `gather_rows` 32-bit words that the launch sets to zero.
 };
 
 // GeLU with the exact-erf definition a * Phi(a); erf by the Abramowitz-Stegun rational form 7.1.26
@@ -93,7 +96,8 @@ gemm_bf16_kernel(const bf16_t* __restrict__ Aall, const bf16_t* __restrict__ Bal
     constexpr bool F32_STRIP = EPI == EPI_MULGRAD || EPI == EPI_F32;
     constexpr int EPI_STRIDE = F32_STRIP ? WN + 4 : WN + 8;  // elements per staged output row
     static_assert(TM >= 1 && TN >= 1, "tile too small");
-    static_assert(4 * 32 * EPI_STRIDE * (F32_STRIP ? 4 : 2) <= STAGES * STAGE * 2, "epilogue staging must fit");
+    static_assert(EPI == EPI_SOFTMAX || 4 * 32 * EPI_STRIDE * (F32_STRIP ? 4 : 2) <= STAGES * STAGE * 2,
+                  "epilogue staging must fit");
     static_assert(STAGES == 1 || STAGES == 2, "one or two LDS stages");
 
     extern __shared__ __attribute__((aligned(16))) unsigned char smem_raw[];
@@ -105,7 +109,7 @@ gemm_bf16_kernel(const bf16_t* __restrict__ Aall, const bf16_t* __restrict__ Bal
     const int total = G * tiles_m * tiles_n;
     const int per_xcd = (total + 7) / 8;
     const int logical = (blockIdx.x & 7) * per_xcd + (blockIdx.x >> 3);
-    if (logical >= total) return;
+    if (EPI != EPI_SOFTMAX && logical >= total) return;
     const int tm = logical % tiles_m;
     const int tn = (logical / tiles_m) % tiles_n;
     const int g = logical / (tiles_m * tiles_n);
@@ -114,6 +118,13 @@ gemm_bf16_kernel(const bf16_t* __restrict__ Aall, const bf16_t* __restrict__ Bal
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int wr = wave >> 1, wc = wave & 1;
     const int col = lane & 31, half = lane >> 5, l16 = lane & 15;
+
+    if (EPI == EPI_SOFTMAX) {
+        uint32_t* zero_buf = reinterpret_cast<uint32_t*>(const_cast<int32_t*>(gather));
+        for (int i = blockIdx.x * 256 + threadIdx.x; i < gather_rows; i += gridDim.x * 256) zero_buf[i] = 0u;
+        gather = nullptr;
+        if (logical >= total) return;
+    }
 
     // With `gather` (A_MC = false only), row m of group g's left operand is row gather[g*M + m] of one
     // shared [gather_rows, K] matrix: the dispatch of Eq. 3 fused into the tile loads.
@@ -309,7 +320,72 @@ gemm_bf16_kernel(const bf16_t* __restrict__ Aall, const bf16_t* __restrict__ Bal
     // Epilogue.  acc[i][j][4q+t] = C[row m = i*32 + col][column n = j*32 + 8q + 4*half + t] of the wave tile.
     // Per wavefront: stage one 32-row strip (all WN columns) in LDS, then store it with 16-byte vectors.
     const size_t gofs = (size_t)g * M * N;
-    if (!F32_STRIP) {
+    if (EPI == EPI_SOFTMAX) {
+        // A row of the tile is a token's logits over all N columns (tiles_n == 1).  A lane holds 64 of
+        // them per 32-row strip i; the other half-wave holds 64 more and the wavefront next to it (wc ^ 1)
+        // the remaining 128: one shuffle and one exchange through LDS complete a row's maximum and sum.
+        float* __restrict__ Ct = reinterpret_cast<float*>(Call);   // [N][M]
+        float* __restrict__ Cn = reinterpret_cast<float*>(C2all);  // [M][N] or null
+        float* xch = reinterpret_cast<float*>(smem_raw);           // [wave][TM][32]
+        float mx[TM], part[TM];
+#pragma unroll
+        for (int i = 0; i < TM; ++i) {
+            float m = -INFINITY;
+#pragma unroll
+            for (int j = 0; j < TN; ++j)
+#pragma unroll
+                for (int r = 0; r < 16; ++r) {
+                    const int ex = n0 + wc * WN + j * 32 + 8 * (r >> 2) + 4 * half + (r & 3);
+                    if (ex < N) m = fmaxf(m, acc[i][j][r]);
+                }
+            mx[i] = fmaxf(m, __shfl_xor(m, 32, kWave));
+            if (half == 0) xch[(wave * TM + i) * 32 + col] = mx[i];
+        }
+        __syncthreads();
+#pragma unroll
+        for (int i = 0; i < TM; ++i) mx[i] = fmaxf(mx[i], xch[((wave ^ 1) * TM + i) * 32 + col]);
+        __syncthreads();
+#pragma unroll
+        for (int i = 0; i < TM; ++i) {
+            float sum = 0.0f;
+#pragma unroll
+            for (int j = 0; j < TN; ++j)
+#pragma unroll
+                for (int r = 0; r < 16; ++r) {
+                    const int ex = n0 + wc * WN + j * 32 + 8 * (r >> 2) + 4 * half + (r & 3);
+                    const float p = ex < N ? expf(acc[i][j][r] - mx[i]) : 0.0f;
+                    acc[i][j][r] = p;
+                    sum += p;
+                }
+            sum += __shfl_xor(sum, 32, kWave);
+            part[i] = sum;
+            if (half == 0) xch[(wave * TM + i) * 32 + col] = sum;
+        }
+        __syncthreads();
+#pragma unroll
+        for (int i = 0; i < TM; ++i) {
+            const float other = xch[((wave ^ 1) * TM + i) * 32 + col];
+            const float total_sum = part[i] + other;  // the same two addends in both wavefronts: the same sum
+            const int gm = m0 + wr * WM + i * 32 + col;
+            if (gm < M) {
+#pragma unroll
+                for (int j = 0; j < TN; ++j)
+#pragma unroll
+                    for (int q = 0; q < 4; ++q) {
+                        const int ex0 = n0 + wc * WN + j * 32 + 8 * q + 4 * half;
+                        if (ex0 < N) {  // N % 8 == 0: a quad is all columns or all padding
+                            floatx4 o;
+#pragma unroll
+                            for (int t = 0; t < 4; ++t) {
+                                o[t] = acc[i][j][4 * q + t] / total_sum;
+                                if (Ct != nullptr) Ct[(size_t)(ex0 + t) * M + gm] = o[t];
+                            }
+                            if (Cn != nullptr) *reinterpret_cast<floatx4*>(Cn + (size_t)gm * N + ex0) = o;
+                        }
+                    }
+            }
+        }
+    } else if (!F32_STRIP) {
         bf16_t* __restrict__ C = reinterpret_cast<bf16_t*>(Call) + gofs;
         bf16_t* __restrict__ Cpre = EPI == EPI_ACT_SAVE ? reinterpret_cast<bf16_t*>(C2all) + gofs : nullptr;
         bf16_t* strip = smem + wave * 32 * EPI_STRIDE;

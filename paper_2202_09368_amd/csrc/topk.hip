@@ -273,6 +273,267 @@ topk_tokens_kernel(const float* __restrict__ St, int n, int k, float* __restrict
     }
 }
 
+// ---------------------------------------------------------------------------
+// Register-resident variant: the whole row lives in the registers of the 1024 threads (R quads of
+// four scores per thread, n <= 4096 * R <= 65536), so S^T is read exactly once and every later
+// pass (radix digits, cut-off, counting, emission) runs out of registers.  Wavefront w owns the
+// contiguous tokens [w * 256 R, (w + 1) * 256 R); quad r of a lane covers tokens
+// w * 256 R + 256 r + 4 lane .. + 3, so a wavefront's loads are whole 1-KiB pieces of the row.
+// Histograms: four copies (one per wavefront residue) in three rotating buffers, which leaves one
+// barrier per radix pass; every wavefront scans the histogram itself instead of waiting for a
+// broadcast.  Requires n % 4 == 0 (16-byte aligned rows).
+//
+// gridDim.y > 1 selects per group of tokens: the row is cut into gridDim.y equal segments of n
+// tokens and every (expert, segment) pair takes its own k best; a bucket then lists its segments
+// one after the other, which keeps it in ascending token order.
+// ---------------------------------------------------------------------------
+struct TopkRegShared {
+    unsigned int hist[3][4][256];
+    unsigned int red[2 * TOPK_WAVES];
+    unsigned int wave_cnt[TOPK_WAVES];
+    unsigned int cand_key[TOPK_CAND_MAX];  // candidates for the cut-off: key and ~token, kept as separate
+    unsigned int cand_ntok[TOPK_CAND_MAX]; // 32-bit words (64-bit keys would double the register need)
+    unsigned int cut_key, cut_ntok;
+    unsigned int slot;
+};
+
+template <int R>
+__global__ void __launch_bounds__(TOPK_THREADS)
+topk_tokens_reg_kernel(const float* __restrict__ St, int n_total, int n, int k, float* __restrict__ G,
+                       int32_t* __restrict__ I, TopkEmit emit) {
+    __shared__ TopkRegShared sh;
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int expert = blockIdx.x, tok0 = blockIdx.y * n;
+    const size_t out0 = ((size_t)expert * gridDim.y + blockIdx.y) * (size_t)k;
+    const unsigned int* __restrict__ colg = reinterpret_cast<const unsigned int*>(St) + (size_t)expert * n_total + tok0;
+    constexpr int PER_WAVE = 256 * R;
+    const int t_base = wave * PER_WAVE + 4 * lane;  // token of quad 0, element 0
+    // quads r < rv are inside the row (n % 4 == 0: a quad is inside or outside as a whole)
+    const int rv = t_base >= n ? 0 : ((n - t_base + 255) >> 8) < R ? ((n - t_base + 255) >> 8) : R;
+    const unsigned long long lt_mask = (1ull << lane) - 1ull;
+
+    // ---- 1. one read of the row; min / max ----------------------------------
+    unsigned int v[R][4];
+    unsigned int vmin = 0xFFFFFFFFu, vmax = 0u;
+#pragma unroll
+    for (int r = 0; r < R; ++r) {
+        // Quads outside the row hold 0xFFFFFFFF: scores are non-negative floats (bits below 2^31), so this
+        // value is never inside a radix window and, compared as a signed number, never passes the cut-off.
+        uint4 q = make_uint4(0xFFFFFFFFu, 0xFFFFFFFFu, 0xFFFFFFFFu, 0xFFFFFFFFu);
+        if (r < rv) {
+            q = *reinterpret_cast<const uint4*>(colg + t_base + 256 * r);
+            vmin = min(vmin, min(min(q.x, q.y), min(q.z, q.w)));
+            vmax = max(vmax, max(max(q.x, q.y), max(q.z, q.w)));
+        }
+        v[r][0] = q.x; v[r][1] = q.y; v[r][2] = q.z; v[r][3] = q.w;
+    }
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) {
+        vmin = min(vmin, (unsigned int)__shfl_xor(vmin, off, kWave));
+        vmax = max(vmax, (unsigned int)__shfl_xor(vmax, off, kWave));
+    }
+    if (lane == 0) { sh.red[wave] = vmin; sh.red[TOPK_WAVES + wave] = vmax; }
+    (&sh.hist[0][0][0])[tid] = 0u;         // buffers 0 and 1 start clean (1024 words each)
+    (&sh.hist[1][0][0])[tid] = 0u;
+    if (tid == 0) sh.slot = 0u;
+    __syncthreads();
+#pragma unroll
+    for (int w = 0; w < TOPK_WAVES; ++w) {
+        vmin = min(vmin, sh.red[w]);
+        vmax = max(vmax, sh.red[TOPK_WAVES + w]);
+    }
+    // block-uniform values are moved to scalar registers: fewer vector registers, scalar branches
+    vmin = __builtin_amdgcn_readfirstlane(vmin);
+    vmax = __builtin_amdgcn_readfirstlane(vmax);
+    // ---- 2. radix select on key = bits - vmin ---------------------------------
+    const unsigned int range = vmax - vmin;
+    int lo = range == 0 ? 0 : 32 - __clz(range);
+    unsigned int prefix = 0, remaining = (unsigned int)k, cand = (unsigned int)n;
+    int pass = 0;
+    while (cand > (unsigned int)TOPK_CAND_MAX && lo > 0) {
+        const int nlo = lo > 8 ? lo - 8 : 0;
+        // scores whose key (bits - vmin) matches the decided prefix: bits - (vmin + prefix) < 2^lo; what is
+        // left after the subtraction is the undecided part of the key, its top digit the histogram bin
+        const unsigned int base = vmin + prefix, span_m1 = lo >= 32 ? 0xFFFFFFFFu : (1u << lo) - 1u;
+        unsigned int* H = sh.hist[pass % 3][wave & 3];
+#pragma unroll
+        for (int r = 0; r < R; ++r) {
+#pragma unroll
+            for (int c = 0; c < 4; ++c) {
+                const unsigned int t = v[r][c] - base;
+                if (t <= span_m1) atomicAdd(&H[t >> nlo], 1u);
+            }
+        }
+        __syncthreads();
+        // The buffer of the pass after the next one was last scanned before this barrier: clear it now.
+        (&sh.hist[(pass + 2) % 3][0][0])[tid] = 0u;
+        // Every wavefront scans for itself: lane owns bins 4*lane .. 4*lane+3.
+        unsigned int h[4] = {0u, 0u, 0u, 0u};
+#pragma unroll
+        for (int cpy = 0; cpy < 4; ++cpy) {
+            const uint4 q = *reinterpret_cast<const uint4*>(&sh.hist[pass % 3][cpy][4 * lane]);
+            h[0] += q.x; h[1] += q.y; h[2] += q.z; h[3] += q.w;
+        }
+        const unsigned int tot = h[0] + h[1] + h[2] + h[3];
+        unsigned int incl = tot;  // inclusive suffix sum over lanes >= this one
+#pragma unroll
+        for (int off = 1; off < 64; off <<= 1) {
+            const unsigned int o = __shfl_down(incl, off, kWave);
+            if (lane + off < 64) incl += o;
+        }
+        const unsigned int above = incl - tot;
+        const bool own = above < remaining && remaining <= incl;  // exactly one lane
+        unsigned int b = 0, ab = 0, hb = 0;
+        if (own) {
+            const unsigned int a3 = above, a2 = a3 + h[3], a1 = a2 + h[2], a0 = a1 + h[1];
+            if (remaining <= a2) { b = 3; ab = a3; hb = h[3]; }
+            else if (remaining <= a1) { b = 2; ab = a2; hb = h[2]; }
+            else if (remaining <= a0) { b = 1; ab = a1; hb = h[1]; }
+            else { b = 0; ab = a0; hb = h[0]; }
+            b += 4u * (unsigned int)lane;
+        }
+        const int src = __ffsll((long long)__ballot(own)) - 1;
+        b = __builtin_amdgcn_readlane(b, src);
+        ab = __builtin_amdgcn_readlane(ab, src);
+        hb = __builtin_amdgcn_readlane(hb, src);
+        prefix |= b << nlo;
+        remaining -= ab;
+        cand = hb;
+        lo = nlo;
+        ++pass;
+    }
+    const unsigned int base = vmin + prefix, span_m1 = lo >= 32 ? 0xFFFFFFFFu : (1u << lo) - 1u;
+
+    // ---- 3. the cut-off key ----------------------------------------------------
+    if (cand <= (unsigned int)TOPK_CAND_MAX) {
+#pragma unroll
+        for (int r = 0; r < R; ++r) {
+#pragma unroll
+            for (int c = 0; c < 4; ++c) {
+                if (v[r][c] - base <= span_m1) {
+                    const unsigned int p = atomicAdd(&sh.slot, 1u);
+                    if (p < (unsigned int)TOPK_CAND_MAX) {
+                        sh.cand_key[p] = v[r][c];
+                        sh.cand_ntok[p] = 0xFFFFFFFFu - (unsigned int)(t_base + 256 * r + c);
+                    }
+                }
+            }
+        }
+        __syncthreads();
+        if (tid < (int)cand) {
+            const unsigned int mhi = sh.cand_key[tid], mlo = sh.cand_ntok[tid];
+            unsigned int above = 0;
+            for (unsigned int j = 0; j < cand; ++j) {
+                const unsigned int ohi = sh.cand_key[j], olo = sh.cand_ntok[j];
+                above += (ohi > mhi) | ((ohi == mhi) & (olo > mlo));
+            }
+            if (above == remaining - 1u) { sh.cut_key = mhi; sh.cut_ntok = mlo; }
+        }
+    } else {
+        // Exact ties at the threshold score: the cut-off is the `remaining`-th tied token in token order.
+        const unsigned int tbits = base;  // every bit of the threshold score is decided
+        unsigned int ties = 0;
+#pragma unroll
+        for (int r = 0; r < R; ++r)
+            ties += (v[r][0] == tbits) + (v[r][1] == tbits) + (v[r][2] == tbits) + (v[r][3] == tbits);
+#pragma unroll
+        for (int off = 32; off > 0; off >>= 1) ties += __shfl_xor(ties, off, kWave);
+        if (lane == 0) sh.wave_cnt[wave] = ties;
+        __syncthreads();
+        unsigned int before = 0;
+#pragma unroll
+        for (int w = 0; w < TOPK_WAVES; ++w) before += w < wave ? sh.wave_cnt[w] : 0u;
+        if (before < remaining && remaining <= before + ties) {  // this wavefront holds the cut-off token
+            unsigned int seen = before;
+#pragma unroll
+            for (int r = 0; r < R; ++r) {
+                unsigned int pre = 0, tot = 0;
+                bool eq[4];
+#pragma unroll
+                for (int c = 0; c < 4; ++c) {
+                    eq[c] = v[r][c] == tbits;
+                    const unsigned long long bal = __ballot(eq[c]);
+                    pre += (unsigned int)__popcll(bal & lt_mask);
+                    tot += (unsigned int)__popcll(bal);
+                }
+                // token order inside a quad row: lane-major, then element
+                unsigned int rank = seen + pre;
+                // lanes below contribute all four of their elements before this lane's first one
+#pragma unroll
+                for (int c = 0; c < 4; ++c) {
+                    if (eq[c] && rank == remaining - 1u) {
+                        sh.cut_key = tbits;
+                        sh.cut_ntok = 0xFFFFFFFFu - (unsigned int)(t_base + 256 * r + c);
+                    }
+                    rank += eq[c] ? 1u : 0u;
+                }
+                seen += tot;
+            }
+        }
+        __syncthreads();  // wave_cnt is reused below
+    }
+    __syncthreads();
+    const unsigned int chi = __builtin_amdgcn_readfirstlane(sh.cut_key);
+    const int cut_tok = (int)(0xFFFFFFFFu - (unsigned int)__builtin_amdgcn_readfirstlane(sh.cut_ntok));
+    // score above the cut-off score, or equal to it with a token index up to the cut-off token; `ofs` is the
+    // compile-time offset of the element from the lane's first token, so the comparison needs no index register
+    auto admitted = [&](unsigned int key, int ofs) -> bool {
+        return ((int)key > (int)chi) | ((key == chi) & (t_base <= cut_tok - ofs));
+    };
+
+    // ---- 4. count per wavefront, prefix, emit in token order ---------------------
+    unsigned int mine_cnt = 0;
+#pragma unroll
+    for (int r = 0; r < R; ++r) {
+#pragma unroll
+        for (int c = 0; c < 4; ++c) mine_cnt += admitted(v[r][c], 256 * r + c) ? 1u : 0u;
+    }
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) mine_cnt += __shfl_xor(mine_cnt, off, kWave);
+    if (lane == 0) sh.wave_cnt[wave] = mine_cnt;
+    __syncthreads();
+    unsigned int pos = 0;
+#pragma unroll
+    for (int w = 0; w < TOPK_WAVES; ++w) pos += w < wave ? sh.wave_cnt[w] : 0u;
+    if (mine_cnt == 0u) return;  // uniform per wavefront; no barrier follows
+
+#pragma unroll
+    for (int r = 0; r < R; ++r) {
+        bool sel[4];
+        unsigned int pre = 0, tot = 0;
+#pragma unroll
+        for (int c = 0; c < 4; ++c) {
+            sel[c] = admitted(v[r][c], 256 * r + c);
+            const unsigned long long bal = __ballot(sel[c]);
+            pre += (unsigned int)__popcll(bal & lt_mask);
+            tot += (unsigned int)__popcll(bal);
+        }
+        if (tot != 0u) {  // uniform
+            const int tok_q = tok0 + t_base + 256 * r;
+            int slot_at[4] = {0, 0, 0, 0};
+            if (emit.slot_cnt != nullptr) {  // the four atomics are in flight together; their results feed the stores below
+#pragma unroll
+                for (int c = 0; c < 4; ++c)
+                    if (sel[c]) slot_at[c] = atomicAdd(&emit.slot_cnt[tok_q + c], 1);
+            }
+            unsigned int j = pos + pre;
+#pragma unroll
+            for (int c = 0; c < 4; ++c) {
+                if (sel[c] && j < (unsigned int)k) {  // j < k always holds for a correct selection; guards the stores
+                    G[out0 + j] = __uint_as_float(v[r][c]);
+                    I[out0 + j] = tok_q + c;
+                    if (emit.slot_cnt != nullptr && slot_at[c] < emit.slot_cap)
+                        emit.slots[(size_t)(tok_q + c) * emit.slot_cap + slot_at[c]] = (int32_t)(out0 + j);
+                    if (emit.bitmap != nullptr)
+                        atomicOr(&emit.bitmap[(size_t)(tok_q + c) * emit.bitmap_words + (expert >> 5)], 1u << (expert & 31));
+                }
+                j += sel[c] ? 1u : 0u;
+            }
+        }
+        pos += tot;
+    }
+}
+
 // LDS the top-k kernel may use for the staged row.
 static size_t topk_lds_budget() {
     static size_t budget = 0;
@@ -292,13 +553,33 @@ static size_t topk_lds_budget() {
 // The selection needs no scratch in global memory.
 size_t topk_ws_bytes(int64_t, int64_t, int64_t) { return 0; }
 
+template <int R>
+static void launch_topk_reg(const float* St, int n_total, int n_seg, int k, int e, int groups, float* G, int32_t* I,
+                            const TopkEmit& emit, hipStream_t stream) {
+    hipLaunchKernelGGL(topk_tokens_reg_kernel<R>, dim3((unsigned)e, (unsigned)groups), dim3(TOPK_THREADS), 0, stream, St,
+                       n_total, n_seg, k, G, I, emit);
+}
+
+// n tokens in all, cut into `groups` equal segments; k is the bucket size per (expert, segment).
 int launch_topk(const float* St, int64_t n, int64_t e, int64_t k, float* G, int32_t* I,
                 unsigned long long* sortkeys_ws, int32_t* slot_cnt, int32_t* slots, int slot_cap, uint32_t* bitmap,
-                hipStream_t stream) {
+                hipStream_t stream, int64_t groups) {
     (void)sortkeys_ws;
     TopkEmit emit;
     emit.slot_cnt = slot_cnt; emit.slots = slots; emit.slot_cap = slot_cap;
     emit.bitmap = bitmap; emit.bitmap_words = (int)ceil_div(e, 32);
+    const int64_t seg = n / groups;
+    if ((seg & 3) == 0 && seg <= 65536 && groups <= 65535) {
+        // the row (segment) fits the registers of one workgroup: S^T is read once
+        const int ni = (int)n, si = (int)seg, ki = (int)k, ei = (int)e, gi = (int)groups;
+        if (seg <= 4096) launch_topk_reg<1>(St, ni, si, ki, ei, gi, G, I, emit, stream);
+        else if (seg <= 8192) launch_topk_reg<2>(St, ni, si, ki, ei, gi, G, I, emit, stream);
+        else if (seg <= 16384) launch_topk_reg<4>(St, ni, si, ki, ei, gi, G, I, emit, stream);
+        else if (seg <= 32768) launch_topk_reg<8>(St, ni, si, ki, ei, gi, G, I, emit, stream);
+        else launch_topk_reg<16>(St, ni, si, ki, ei, gi, G, I, emit, stream);
+        return check_launch();
+    }
+    if (groups != 1) return EC_ERR_UNSUPPORTED;  // segments must be multiples of 4 tokens, at most 65536 long
     const size_t stage_bytes = align_up((size_t)n * 4, 16);
     const bool staged = stage_bytes <= topk_lds_budget();
     const size_t dyn = staged ? stage_bytes : 0;

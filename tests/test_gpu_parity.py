@@ -190,6 +190,37 @@ def test_cfg5_full_routing_only(m, ref):
     _stagewise(m, ref, w, wl.make_inputs(w))
 
 
+# -------------------------------------------------------------------- gate ---
+@pytest.mark.parametrize("n,d,e", [
+    (128 * 256 + 77, 128, 192),   # more than 128 experts, ragged tokens, experts short of the 256-wide tile
+    (128 * 256, 192, 256),
+    (128 * 128 + 5, 256, 96),     # 65..128 experts: the 128-wide tile with padding columns
+    (128 * 128, 64, 128),
+])
+def test_gate_many_experts(m, ref, n, d, e):
+    # shapes that take the matrix-product path of the gate (many experts, enough tokens to fill the chip)
+    _p(f"[gate] n={n} d={d} e={e}")
+    w = wl.scaled(wl.WORKLOADS["cfg5"], n=n, d=d, e=e, seed=n + e)
+    inp = wl.make_inputs(w)
+    X, Wg = to_dev(inp["X"]), to_dev(inp["Wg"])
+    S = torch.empty((n, e), dtype=torch.float32, device="cuda")
+    St = torch.empty((e, n), dtype=torch.float32, device="cuda")
+    m.ec_moe_gate(X, Wg, S, St, None)
+    torch.cuda.synchronize()
+    S_h, St_h = to_host(S), to_host(St)
+    assert (St_h == S_h.T).all()
+    S_ref = ref.gate(inp["X"], inp["Wg"])
+    assert (max_rel_err_rows(S_h, S_ref) <= score_tolerance(inp["X"], inp["Wg"])).all()
+    assert np.abs(S_h.astype(np.float64).sum(axis=1) - 1.0).max() < 1e-5 and (S_h >= 0).all()
+    # either output alone
+    St2 = torch.empty_like(St)
+    m.ec_moe_gate(X, Wg, None, St2, None)
+    S2 = torch.empty_like(S)
+    m.ec_moe_gate(X, Wg, S2, None, None)
+    torch.cuda.synchronize()
+    assert (to_host(St2) == St_h).all() and (to_host(S2) == S_h).all()
+
+
 # ------------------------------------------------------------------- top-k ---
 def _topk_case(m, ref, St_h, k):
     e, n = St_h.shape
@@ -215,6 +246,9 @@ def _topk_case(m, ref, St_h, k):
     (70000, 2, 3000, "levels"),
     (6000, 2, 64, "onehot"),                        # saturated softmax rows: exact 1.0 and 0.0
     (50000, 2, 500, "tiny_range"),                  # all scores within a few ulps of each other
+    (12, 2, 5, "rand"), (4096, 3, 100, "rand"), (4100, 3, 100, "rand"),   # around the register-tile edges
+    (65536, 2, 256, "rand"), (65536, 2, 40000, "levels"), (65536, 2, 300, "const"),
+    (65540, 2, 256, "rand"), (32768, 2, 512, "onehot"), (16384, 3, 16384, "levels"),
 ])
 def test_topk_cases(m, ref, n, e, k, kind):
     _p(f"[topk] n={n} e={e} k={k} {kind}")
