@@ -35,7 +35,8 @@ bfloat16 tensors arrive as uint16 bit patterns and are widened exactly.
 parity pins: every function here is pinned by tests/test_oracle_pins.py
 (brute-force selection, dense one-hot einsum of Eq. 3/4, closed forms for
 degenerate routings, textbook dense FFN for e=1, finite differences and an
-autograd restatement for the backward).
+autograd restatement for the backward; routing per group against the plain
+layer run on each group as a batch of its own and a brute-force selection).
 """
 from __future__ import annotations
 
@@ -201,6 +202,60 @@ def forward(X, Wg, W1, W2, c: float, act: int) -> Dict[str, np.ndarray]:
         X_e = expert_ffn(X_in, W1, W2, act)
     X_out = combine(X_e, G, I, n)
     return {"k": k, "S": S, "G": G, "I": I, "X_in": X_in, "X_e": X_e, "X_out": X_out}
+
+
+# ------------------------------------------------------- routing per group ---
+# Limitations section: expert choice looks at every token of the batch, future ones included; the
+# proposed remedy is to cut the batch into groups and let every expert choose inside each group
+# separately.  Reading taken here: the n tokens are cut into `groups` equal runs of consecutive
+# tokens (the caller lays the batch out so that a run is what must be routed together, e.g. one
+# position of many sequences); every (expert, group) pair keeps k_g = floor((n/groups)*c/e) tokens;
+# an expert's bucket lists group 0's tokens, then group 1's, and so on, each by ascending index.
+def topk_tokens_grouped(S: np.ndarray, k_g: int, groups: int) -> Tuple[np.ndarray, np.ndarray]:
+    """Per group g and expert i: the k_g best of S[g*n_g:(g+1)*n_g, i]; ties to the lower index.
+
+    Returns G, I of shape [e, groups*k_g]; I holds indices into the whole batch.
+    """
+    S = np.asarray(S)
+    if S.dtype != np.float32:
+        raise TypeError("TopK acts on the float32 scores")
+    n, e = S.shape
+    if groups < 1 or n % groups != 0:
+        raise ValueError("the groups must cut the batch into equal parts")
+    n_g = n // groups
+    if not (1 <= k_g <= n_g):
+        raise ValueError("k_g outside [1, n/groups]")
+    I = np.empty((e, groups * k_g), dtype=np.int32)
+    G = np.empty((e, groups * k_g), dtype=np.float32)
+    for g in range(groups):
+        first = g * n_g
+        for i in range(e):
+            col = S[first:first + n_g, i]
+            order = np.lexsort((np.arange(n_g), -col.astype(np.float64)))   # by score descending, then index
+            chosen = np.sort(order[:k_g]) + first
+            I[i, g * k_g:(g + 1) * k_g] = chosen
+            G[i, g * k_g:(g + 1) * k_g] = S[chosen, i]
+    return G, I
+
+
+def forward_grouped(X, Wg, W1, W2, c: float, act: int, groups: int) -> Dict[str, np.ndarray]:
+    """The layer of Eq. 1-4 with the TopK of Eq. 2 taken inside each group of tokens."""
+    n, d = np.asarray(X).shape
+    e = np.asarray(Wg).shape[1]
+    if groups < 1 or n % groups != 0:
+        raise ValueError("the groups must cut the batch into equal parts")
+    k_g = capacity(n // groups, c, e)
+    S = gate(X, Wg)
+    G, I = topk_tokens_grouped(S, k_g, groups)
+    X_in = dispatch(X, I)
+    if W1 is None:
+        if act != ACT_IDENTITY:
+            raise ValueError("identity experts need act = ACT_IDENTITY")
+        X_e = widen(X_in)
+    else:
+        X_e = expert_ffn(X_in, W1, W2, act)
+    X_out = combine(X_e, G, I, n)
+    return {"k_g": k_g, "S": S, "G": G, "I": I, "X_in": X_in, "X_e": X_e, "X_out": X_out}
 
 
 # ---------------------------------------------------------------- backward ---

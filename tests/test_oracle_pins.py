@@ -421,6 +421,64 @@ def test_backward_one_expert_is_dense_ffn_gradient():
 
 
 # ------------------------------------------------------------- workloads ----
+# ------------------------------------------------------- routing per group ---
+@pytest.mark.parametrize("seed,n,e,groups,k_g,levels", [(0, 24, 3, 4, 2, 0), (1, 30, 2, 3, 10, 0),
+                                                        (2, 32, 4, 2, 5, 3), (3, 12, 2, 12, 1, 0)])
+def test_grouped_topk_against_brute_force(seed, n, e, groups, k_g, levels):
+    r = _rng(seed)
+    S = r.random((n, e)).astype(np.float32)
+    if levels:
+        S = (np.floor(S * levels) / levels).astype(np.float32)
+    G, I = ref.topk_tokens_grouped(S, k_g, groups)
+    n_g = n // groups
+    for i in range(e):
+        expect = []
+        for g in range(groups):   # pure-Python selection inside the group's own tokens
+            expect += [g * n_g + t for t in sorted(_brute_topk(S[g * n_g:(g + 1) * n_g, i].tolist(), k_g))]
+        assert I[i].tolist() == expect
+        assert (G[i] == S[expect, i]).all()
+
+
+def test_grouped_topk_special_cases():
+    r = _rng(11)
+    S = r.random((40, 5)).astype(np.float32)
+    # one group is the plain TopK of Eq. 2
+    G1, I1 = ref.topk_tokens_grouped(S, 7, 1)
+    G0, I0 = ref.topk_tokens(S, 7)
+    assert (I1 == I0).all() and (G1 == G0).all()
+    # k_g = n_g: every expert takes every token, in order
+    G, I = ref.topk_tokens_grouped(S, 10, 4)
+    assert (I == np.arange(40)[None, :]).all() and (G == S.T).all()
+    # a group's selection does not see the other groups: overwrite group 2, groups 0, 1, 3 keep theirs
+    _, Ia = ref.topk_tokens_grouped(S, 3, 4)
+    S2 = S.copy()
+    S2[20:30] = r.random((10, 5)).astype(np.float32)
+    _, Ib = ref.topk_tokens_grouped(S2, 3, 4)
+    keep = np.r_[0:6, 9:12]
+    assert (Ia[:, keep] == Ib[:, keep]).all()
+    # every expert holds exactly k_g tokens of every group
+    for g in range(4):
+        seg = Ia[:, 3 * g:3 * g + 3]
+        assert ((seg >= 10 * g) & (seg < 10 * g + 10)).all()
+
+
+@pytest.mark.parametrize("act", [wl.ACT_GELU, wl.ACT_IDENTITY])
+def test_grouped_layer_is_the_plain_layer_on_every_group(act):
+    # routing per group == running Eq. 1-4 on each group as a batch of its own
+    w = wl.scaled(wl.WORKLOADS["cfg1"], n=48, d=8, e=4, c=2.0, d_ff=16, act=act, seed=21)
+    inp = wl.make_inputs(w)
+    groups = 4
+    n_g = w.n // groups
+    W1, W2 = (inp["W1"], inp["W2"]) if act != wl.ACT_IDENTITY else (None, None)
+    out = ref.forward_grouped(inp["X"], inp["Wg"], W1, W2, w.c, act, groups)
+    assert out["k_g"] == ref.capacity(n_g, w.c, w.e)
+    for g in range(groups):
+        sub = ref.forward(inp["X"][g * n_g:(g + 1) * n_g], inp["Wg"], W1, W2, w.c, act)
+        np.testing.assert_allclose(out["X_out"][g * n_g:(g + 1) * n_g], sub["X_out"], rtol=1e-12, atol=1e-14)
+        seg = out["I"][:, g * out["k_g"]:(g + 1) * out["k_g"]]
+        assert (seg == sub["I"] + g * n_g).all()
+
+
 def test_workload_generators_are_seeded_and_shaped():
     w = wl.WORKLOADS["cfg1"]
     a, b = wl.make_inputs(w), wl.make_inputs(w)
