@@ -41,6 +41,8 @@ def parse_args():
     ap.add_argument("--warmup", type=int, default=10)
     ap.add_argument("--workload", default="cfg2",
                     help="cfg2 (headline), cfg3, cfg5 (routing only), cfg4 (forward + backward)")
+    ap.add_argument("--groups", type=int, default=1,
+                    help="expert choice inside this many equal runs of tokens (1: the paper's global TopK)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--copy-calibration", type=int, default=0, metavar="MiB",
                     help="only run a plain device-to-device copy of this many MiB five times (reference "
@@ -78,6 +80,12 @@ def main() -> int:
 
     w = wl.WORKLOADS[args.workload]
     n, d, e, k, d_ff = w.n, w.d, w.e, w.k, w.d_ff
+    groups = args.groups
+    if groups < 1 or n % groups != 0 or (groups > 1 and w.backward):
+        print("bench.py: --groups must divide the token count (forward workloads only)", file=sys.stderr)
+        return 2
+    k_g = m.ec_moe_capacity(n // groups, e, w.c)
+    k = groups * k_g          # rows of an expert's bucket (groups = 1: Eq. 1)
     b = 2 if w.dtype == wl.DTYPE_BF16 else 4
     inp = wl.make_inputs(w, with_dy=False)
 
@@ -115,7 +123,10 @@ def main() -> int:
                               gr["dX"], gr["dWg"], gr["dW1"], gr["dW2"], w.act, ws)
     else:
         def step():
-            m.ec_moe_forward(X, Wg, W1, W2, w.c, Xout, w.act, ws)
+            if groups == 1:
+                m.ec_moe_forward(X, Wg, W1, W2, w.c, Xout, w.act, ws)
+            else:
+                m.ec_moe_forward_grouped(X, Wg, W1, W2, w.c, groups, Xout, w.act, ws)
     for _ in range(W):
         step()
     torch.cuda.synchronize()
@@ -139,7 +150,10 @@ def main() -> int:
         events[0].record()
         m.ec_moe_gate(X, Wg, None, St, ws)
         events[1].record()
-        m.ec_moe_topk_tokens(St, k, G, I, ws)
+        if groups == 1:
+            m.ec_moe_topk_tokens(St, k, G, I, ws)
+        else:
+            m.ec_moe_topk_tokens_grouped(St, groups, k_g, G, I, ws)
         events[2].record()
         m.ec_moe_dispatch(X, I, Xin)
         events[3].record()
@@ -215,7 +229,7 @@ def main() -> int:
         se = e if d_ff == 0 else max(1, min(e, int(8 * (1024 * 768 * 3072) / max(1, k * d * d_ff))))
         t0 = time.perf_counter()
         S_o = ref.gate(inp["X"], inp["Wg"])
-        G_o, I_o = ref.topk_tokens(S_o, k)
+        G_o, I_o = ref.topk_tokens(S_o, k) if groups == 1 else ref.topk_tokens_grouped(S_o, k_g, groups)
         Xin_o = ref.dispatch(inp["X"], I_o)
         t_route = time.perf_counter() - t0
         t_ffn = 0.0
@@ -241,7 +255,8 @@ def main() -> int:
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "bf16" if w.dtype == wl.DTYPE_BF16 else "f32", "data": "synthetic",
         "config": {"workload": f"{w.name}: EC-MoE layer forward{' + backward' if w.backward else ''}, "
-                               f"n={n} d={d} e={e} c={w.c:g} k={k} d_ff={d_ff}",
+                               f"n={n} d={d} e={e} c={w.c:g} k={k} d_ff={d_ff}"
+                               + (f", TopK inside {groups} groups of {n // groups} tokens" if groups > 1 else ""),
                    "act": {0: "relu", 1: "gelu", 2: "identity"}[w.act], "seed": w.seed},
         "roofline": roofline, "cpu_baseline": cpu_baseline, "stages": stages,
     }

@@ -85,6 +85,17 @@ int ec_moe_gate(const void* X, const void* Wg, float* S, float* St,
 int ec_moe_topk_tokens(const float* St, int64_t n, int64_t e, int64_t k,
                        float* G, int32_t* I, void* ws, size_t ws_bytes, void* stream);
 
+/* Limitations section: expert choice inside groups of tokens, so that a selection never looks
+ * outside its group (the remedy proposed there for autoregressive use and small batches).  The n
+ * tokens are `groups` equal runs of consecutive tokens (n % groups == 0); every (expert, group)
+ * pair takes the k_g best of its run, ties and order as in ec_moe_topk_tokens.  G, I [e, groups*k_g]:
+ * an expert's bucket lists group 0's tokens, then group 1's, ...; I holds indices into the whole
+ * batch, so the bucket as a whole is in ascending token order.  1 <= k_g <= n/groups.
+ * EC_ERR_UNSUPPORTED unless groups == 1 or a run is a multiple of 4 and at most 65536 tokens.
+ * ws is not used (NULL, 0 allowed). */
+int ec_moe_topk_tokens_grouped(const float* St, int64_t n, int64_t e, int64_t groups, int64_t k_g,
+                               float* G, int32_t* I, void* ws, size_t ws_bytes, void* stream);
+
 /* Sec. 3.2, Eq. 3 (first line), the "shuffle" stage of Sec. 3.4:
  * X_in[i,j,:] = X[I[i,j],:].  X [n,d], X_in [e,k,d] in `dtype`; a bit-exact
  * copy.  Every I[i,j] must lie in [0,n) (not checked on the device). */
@@ -126,6 +137,16 @@ int ec_moe_forward(const void* X, const void* Wg, const void* W1, const void* W2
                    void* Xin_out, void* A_out, void* H_out, void* Xe_out,
                    int64_t n, int64_t d, int64_t e, int64_t d_ff, int act, int dtype,
                    void* ws, size_t ws_bytes, void* stream);
+
+/* ec_moe_forward with the TopK of Eq. 2 taken inside each of `groups` equal runs of tokens (see
+ * ec_moe_topk_tokens_grouped): k_g = floor((n/groups)*c/e) per (expert, group), buckets of
+ * k = groups*k_g rows.  Workspace and optional outputs as in ec_moe_forward with that k.
+ * groups = 1 is ec_moe_forward. */
+int ec_moe_forward_grouped(const void* X, const void* Wg, const void* W1, const void* W2, double c,
+                           int64_t groups, void* Xout, float* S_out, float* G_out, int32_t* I_out,
+                           void* Xin_out, void* A_out, void* H_out, void* Xe_out,
+                           int64_t n, int64_t d, int64_t e, int64_t d_ff, int act, int dtype,
+                           void* ws, size_t ws_bytes, void* stream);
 
 /* Gradient of <dY, X_out> through Eq. 2-4 with the selection I held constant
  * and the gate values G differentiable (Sec. 3.4: the gating network is

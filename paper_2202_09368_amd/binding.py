@@ -46,6 +46,9 @@ _SIGNATURES = {
     "ec_moe_combine": (c_int, [_P, _P, _P, _P, _I64, _I64, _I64, _I64, c_int, _P, _SZ, _P]),
     "ec_moe_forward": (c_int, [_P, _P, _P, _P, c_double, _P, _P, _P, _P, _P, _P, _P, _P,
                                _I64, _I64, _I64, _I64, c_int, c_int, _P, _SZ, _P]),
+    "ec_moe_topk_tokens_grouped": (c_int, [_P, _I64, _I64, _I64, _I64, _P, _P, _P, _SZ, _P]),
+    "ec_moe_forward_grouped": (c_int, [_P, _P, _P, _P, c_double, _I64, _P, _P, _P, _P, _P, _P, _P, _P,
+                                       _I64, _I64, _I64, _I64, c_int, c_int, _P, _SZ, _P]),
     "ec_moe_backward": (c_int, [_P] * 16 + [_I64] * 5 + [c_int, c_int, _P, _SZ, _P]),
     "ec_moe_last_hip_error": (c_int, []),
     "ec_moe_status_string": (c_char_p, [c_int]),
@@ -175,6 +178,26 @@ def ec_moe_forward(X, Wg, W1, W2, c: float, Xout, act: int, ws, S_out=None, G_ou
     dt = X.dtype
     _check("ec_moe_forward", lib().ec_moe_forward(
         _ptr(X), _ptr(Wg, dt), _ptr(W1, dt), _ptr(W2, dt), c, _ptr(Xout, dt), _ptr(S_out, torch.float32),
+        _ptr(G_out, torch.float32), _ptr(I_out, torch.int32), _ptr(Xin_out, dt), _ptr(A_out, dt), _ptr(H_out, dt),
+        _ptr(Xe_out, dt), n, d, e, d_ff, act, _dtype_code(X), wp, wb, _stream()))
+
+
+def ec_moe_topk_tokens_grouped(St, groups: int, k_g: int, G, I, ws=None) -> None:
+    e, n = St.shape
+    wp, wb = _ws(ws)
+    _check("ec_moe_topk_tokens_grouped", lib().ec_moe_topk_tokens_grouped(
+        _ptr(St, torch.float32), n, e, groups, k_g, _ptr(G, torch.float32), _ptr(I, torch.int32), wp, wb, _stream()))
+
+
+def ec_moe_forward_grouped(X, Wg, W1, W2, c: float, groups: int, Xout, act: int, ws, S_out=None, G_out=None,
+                           I_out=None, Xin_out=None, A_out=None, H_out=None, Xe_out=None) -> None:
+    n, d = X.shape
+    e = Wg.shape[1]
+    d_ff = W1.shape[2] if W1 is not None else 0
+    wp, wb = _ws(ws)
+    dt = X.dtype
+    _check("ec_moe_forward_grouped", lib().ec_moe_forward_grouped(
+        _ptr(X), _ptr(Wg, dt), _ptr(W1, dt), _ptr(W2, dt), c, groups, _ptr(Xout, dt), _ptr(S_out, torch.float32),
         _ptr(G_out, torch.float32), _ptr(I_out, torch.int32), _ptr(Xin_out, dt), _ptr(A_out, dt), _ptr(H_out, dt),
         _ptr(Xe_out, dt), n, d, e, d_ff, act, _dtype_code(X), wp, wb, _stream()))
 

@@ -108,6 +108,16 @@ int ec_moe_topk_tokens(const float* St, int64_t n, int64_t e, int64_t k, float* 
                        (hipStream_t)stream);
 }
 
+int ec_moe_topk_tokens_grouped(const float* St, int64_t n, int64_t e, int64_t groups, int64_t k_g, float* G,
+                               int32_t* I, void* ws, size_t ws_bytes, void* stream) {
+    if (groups <= 0 || n <= 0 || n % groups != 0) return EC_ERR_INVALID_ARG;
+    if (!St || !G || !I || !sizes_ok(n / groups, 1, e, k_g) || !sizes_ok(n, 1, e, groups * k_g) ||
+        !all_aligned(St, G, I))
+        return EC_ERR_INVALID_ARG;
+    (void)ws; (void)ws_bytes;
+    return launch_topk(St, n, e, k_g, G, I, nullptr, nullptr, nullptr, 0, nullptr, (hipStream_t)stream, groups);
+}
+
 int ec_moe_dispatch(const void* X, const int32_t* I, void* Xin, int64_t n, int64_t d, int64_t e, int64_t k,
                     int dtype, void* stream) {
     if (!X || !I || !Xin || !sizes_ok(n, d, e, k) || !dtype_ok(dtype) || !width_ok(d, dtype) ||
@@ -154,12 +164,15 @@ int ec_moe_combine(const void* Xe, const float* G, const int32_t* I, void* Xout,
     return launch_combine(Xe, G, I, Xout, n, d, e, k, dtype, ix, (hipStream_t)stream);
 }
 
-int ec_moe_forward(const void* X, const void* Wg, const void* W1, const void* W2, double c, void* Xout,
-                   float* S_out, float* G_out, int32_t* I_out, void* Xin_out, void* A_out, void* H_out,
-                   void* Xe_out, int64_t n, int64_t d, int64_t e, int64_t d_ff, int act, int dtype, void* ws,
-                   size_t ws_bytes, void* stream) {
-    int64_t k = 0;
-    if (ec_moe_capacity(n, e, c, &k) != EC_OK) return EC_ERR_INVALID_ARG;
+// The layer with TopK taken inside each of `groups` equal runs of tokens (groups = 1: Eq. 2 as printed).
+static int forward_impl(const void* X, const void* Wg, const void* W1, const void* W2, double c, int64_t groups,
+                        void* Xout, float* S_out, float* G_out, int32_t* I_out, void* Xin_out, void* A_out,
+                        void* H_out, void* Xe_out, int64_t n, int64_t d, int64_t e, int64_t d_ff, int act, int dtype,
+                        void* ws, size_t ws_bytes, void* stream) {
+    if (groups <= 0 || n <= 0 || n % groups != 0) return EC_ERR_INVALID_ARG;
+    int64_t k_g = 0;
+    if (ec_moe_capacity(n / groups, e, c, &k_g) != EC_OK) return EC_ERR_INVALID_ARG;
+    const int64_t k = groups * k_g;  // rows of an expert's bucket
     const bool identity = (W1 == nullptr && W2 == nullptr);
     if (!X || !Wg || !Xout || !sizes_ok(n, d, e, k) || !dtype_ok(dtype) || !act_ok(act) || !width_ok(d, dtype) ||
         !all_aligned(X, Wg, W1, W2, Xout, S_out, G_out, I_out, Xin_out, A_out, H_out, Xe_out))
@@ -183,8 +196,9 @@ int ec_moe_forward(const void* X, const void* Wg, const void* W1, const void* W2
     const CombineIndex ix = combine_index_at(ws, L, e);
     int rc = launch_gate(X, Wg, S_out, St, n, d, e, dtype, combine_zero_ptr(ix), combine_zero_words(ix, n, e), st);
     if (rc != EC_OK) return rc;
-    rc = launch_topk(St, n, e, k, G, I, (unsigned long long*)at(ws, L.sortkeys), ix.use_slots ? ix.slot_cnt : nullptr,
-                     ix.slots, ix.slot_cap, ix.use_slots ? nullptr : ix.bitmap, st);
+    rc = launch_topk(St, n, e, k_g, G, I, (unsigned long long*)at(ws, L.sortkeys),
+                     ix.use_slots ? ix.slot_cnt : nullptr, ix.slots, ix.slot_cap, ix.use_slots ? nullptr : ix.bitmap, st,
+                     groups);
     if (rc != EC_OK) return rc;
     // The bucket gather is fused into the first expert product unless the caller wants X_in itself.
     const bool fused_gather = !identity && Xin_out == nullptr && ffn_can_gather(dtype, n, k, d, d_ff);
@@ -201,6 +215,22 @@ int ec_moe_forward(const void* X, const void* Wg, const void* W1, const void* W2
         Xe = Xe_w;
     }
     return launch_combine(Xe, G, I, Xout, n, d, e, k, dtype, ix, st);
+}
+
+int ec_moe_forward(const void* X, const void* Wg, const void* W1, const void* W2, double c, void* Xout,
+                   float* S_out, float* G_out, int32_t* I_out, void* Xin_out, void* A_out, void* H_out,
+                   void* Xe_out, int64_t n, int64_t d, int64_t e, int64_t d_ff, int act, int dtype, void* ws,
+                   size_t ws_bytes, void* stream) {
+    return forward_impl(X, Wg, W1, W2, c, 1, Xout, S_out, G_out, I_out, Xin_out, A_out, H_out, Xe_out, n, d, e, d_ff,
+                        act, dtype, ws, ws_bytes, stream);
+}
+
+int ec_moe_forward_grouped(const void* X, const void* Wg, const void* W1, const void* W2, double c, int64_t groups,
+                           void* Xout, float* S_out, float* G_out, int32_t* I_out, void* Xin_out, void* A_out,
+                           void* H_out, void* Xe_out, int64_t n, int64_t d, int64_t e, int64_t d_ff, int act,
+                           int dtype, void* ws, size_t ws_bytes, void* stream) {
+    return forward_impl(X, Wg, W1, W2, c, groups, Xout, S_out, G_out, I_out, Xin_out, A_out, H_out, Xe_out, n, d, e,
+                        d_ff, act, dtype, ws, ws_bytes, stream);
 }
 
 int ec_moe_backward(const void* dY, const void* X, const void* Wg, const void* W1, const void* W2, const float* S,
