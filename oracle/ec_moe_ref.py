@@ -36,7 +36,9 @@ parity pins: every function here is pinned by tests/test_oracle_pins.py
 (brute-force selection, dense one-hot einsum of Eq. 3/4, closed forms for
 degenerate routings, textbook dense FFN for e=1, finite differences and an
 autograd restatement for the backward; routing per group against the plain
-layer run on each group as a batch of its own and a brute-force selection).
+layer run on each group as a batch of its own and a brute-force selection;
+token-choice routing against a hand-worked example, a per-token brute force,
+the dense top-m mixture when nothing is dropped, and its priority rule).
 """
 from __future__ import annotations
 
@@ -256,6 +258,85 @@ def forward_grouped(X, Wg, W1, W2, c: float, act: int, groups: int) -> Dict[str,
         X_e = expert_ffn(X_in, W1, W2, act)
     X_out = combine(X_e, G, I, n)
     return {"k_g": k_g, "S": S, "G": G, "I": I, "X_in": X_in, "X_e": X_e, "X_out": X_out}
+
+
+# ------------------------------------------- token-choice routing (baseline) ---
+# Sec. 3.1: in conventional routing every token independently picks its top-m experts (m = 1 in
+# Switch Transformer, m = 2 in GShard, Sec. 3.4), an expert can only take a maximum number of tokens,
+# and what is routed to it beyond that is dropped.  The paper states no more than this; the reading
+# taken here, chosen so that the result is unique and the layer around it is Eq. 3-4 unchanged:
+#   * a token's choices are its m largest S[l,:], ties to the lower expert index;
+#   * an expert's buffer has `cap` rows; with cap = floor(n*c/e) (Eq. 1) and c = m the buffers are
+#     as large as expert choice's at the same cost (Sec. 3.4 compares c = 2 with top-2 gating);
+#   * all first choices are placed before any second choice, and inside one rank of choice tokens
+#     are placed by ascending token index; a token that finds the buffer full is dropped there;
+#   * gate weight = the raw score S[l,i] (no renormalisation over the m choices), as in Eq. 4;
+#   * rows of a buffer that stay empty carry I = -1, G = 0 and contribute nothing.
+def token_choice(S: np.ndarray, m: int, cap: int) -> Tuple[np.ndarray, np.ndarray, np.ndarray]:
+    """Returns G [e,cap] float32, I [e,cap] int32 (-1: empty row) and load [e] int32, the number of
+    tokens that chose each expert before anything is dropped (load / cap - 1 is the over-capacity
+    ratio of Sec. 3.1)."""
+    S = np.asarray(S)
+    if S.dtype != np.float32:
+        raise TypeError("routing acts on the float32 scores")
+    n, e = S.shape
+    if not (1 <= m <= e) or cap < 1:
+        raise ValueError("m outside [1, e] or empty buffers")
+    choice = np.empty((n, m), dtype=np.int64)
+    for l in range(n):
+        choice[l] = np.argsort(-S[l], kind="stable")[:m]      # descending score, ties: low expert first
+    I = np.full((e, cap), -1, dtype=np.int32)
+    G = np.zeros((e, cap), dtype=np.float32)
+    fill = np.zeros(e, dtype=np.int64)
+    load = np.zeros(e, dtype=np.int32)
+    for r in range(m):                                         # first choices, then second choices, ...
+        for l in range(n):                                     # by ascending token index
+            i = choice[l, r]
+            load[i] += 1
+            if fill[i] < cap:
+                I[i, fill[i]] = l
+                G[i, fill[i]] = S[l, i]
+                fill[i] += 1
+    return G, I, load
+
+
+def dispatch_padded(X: np.ndarray, I: np.ndarray) -> np.ndarray:
+    """Eq. 3's gather for buffers with empty rows: X_in[i,j,:] = X[I[i,j],:], zeros where I[i,j] = -1."""
+    X = np.asarray(X)
+    out = np.zeros(I.shape + (X.shape[1],), dtype=X.dtype)
+    filled = I >= 0
+    out[filled] = X[I[filled]]
+    return out
+
+
+def combine_padded(X_e: np.ndarray, G: np.ndarray, I: np.ndarray, n: int) -> np.ndarray:
+    """Eq. 4 over the filled rows only; ascending expert order per token as in `combine`."""
+    X_e = widen(X_e)
+    e, k, d = X_e.shape
+    X_out = np.zeros((n, d), dtype=np.float64)
+    for i in range(e):
+        for j in range(k):
+            if I[i, j] >= 0:
+                X_out[I[i, j], :] += float(G[i, j]) * X_e[i, j, :]
+    return X_out
+
+
+def forward_token_choice(X, Wg, W1, W2, c: float, m: int, act: int) -> Dict[str, np.ndarray]:
+    """Gate -> every token's top-m experts with buffers of floor(n*c/e) rows -> Eq. 3 -> Eq. 4."""
+    n, d = np.asarray(X).shape
+    e = np.asarray(Wg).shape[1]
+    cap = capacity(n, c, e)
+    S = gate(X, Wg)
+    G, I, load = token_choice(S, m, cap)
+    X_in = dispatch_padded(X, I)
+    if W1 is None:
+        if act != ACT_IDENTITY:
+            raise ValueError("identity experts need act = ACT_IDENTITY")
+        X_e = widen(X_in)
+    else:
+        X_e = expert_ffn(X_in, W1, W2, act)
+    X_out = combine_padded(X_e, G, I, n)
+    return {"cap": cap, "S": S, "G": G, "I": I, "load": load, "X_in": X_in, "X_e": X_e, "X_out": X_out}
 
 
 # ---------------------------------------------------------------- backward ---

@@ -479,6 +479,108 @@ def test_grouped_layer_is_the_plain_layer_on_every_group(act):
         assert (seg == sub["I"] + g * n_g).all()
 
 
+# ---------------------------------------------------- token-choice routing ---
+def test_token_choice_handworked(golden_dir):
+    with open(os.path.join(golden_dir, "handworked_token_choice.json")) as f:
+        gold = json.load(f)
+    S = np.array(gold["S"], dtype=np.float32)
+    for case in gold["cases"]:
+        G, I, load = ref.token_choice(S, case["m"], case["cap"])
+        assert I.tolist() == case["I"]
+        assert G.tolist() == case["G"]
+        assert load.tolist() == case["load"]
+
+
+def _brute_token_choice(S, m, cap):
+    """Pure Python, token by token: repeated maximum per token, then placement in rank-major order."""
+    n, e = len(S), len(S[0])
+    picks = []
+    for l in range(n):
+        alive = list(range(e))
+        mine = []
+        for _ in range(m):
+            best = alive[0]
+            for i in alive[1:]:
+                if S[l][i] > S[l][best]:
+                    best = i
+            mine.append(best)
+            alive.remove(best)
+        picks.append(mine)
+    rows = [[] for _ in range(e)]
+    load = [0] * e
+    for r in range(m):
+        for l in range(n):
+            i = picks[l][r]
+            load[i] += 1
+            if len(rows[i]) < cap:
+                rows[i].append(l)
+    return rows, load
+
+
+@pytest.mark.parametrize("seed,n,e,m,cap,levels", [(0, 40, 4, 1, 10, 0), (1, 40, 4, 2, 20, 0), (2, 33, 5, 2, 9, 3),
+                                                  (3, 16, 3, 3, 16, 0), (4, 25, 6, 1, 2, 2)])
+def test_token_choice_against_brute_force(seed, n, e, m, cap, levels):
+    r = _rng(seed)
+    S = r.random((n, e)).astype(np.float32)
+    if levels:
+        S = (np.floor(S * levels) / levels).astype(np.float32)
+    G, I, load = ref.token_choice(S, m, cap)
+    rows, load_b = _brute_token_choice(S.tolist(), m, cap)
+    assert load.tolist() == load_b
+    for i in range(e):
+        assert I[i, :len(rows[i])].tolist() == rows[i]
+        assert (I[i, len(rows[i]):] == -1).all() and (G[i, len(rows[i]):] == 0).all()
+        assert (G[i, :len(rows[i])] == S[rows[i], i]).all()
+
+
+def test_token_choice_invariants_and_priority():
+    r = _rng(5)
+    n, e, m, cap = 200, 8, 2, 50
+    S = ref.gate(r.standard_normal((n, 16)).astype(np.float32), 2 * r.standard_normal((16, e)).astype(np.float32))
+    G, I, load = ref.token_choice(S, m, cap)
+    assert load.sum() == n * m                                   # every token makes m choices
+    filled = I >= 0
+    assert (filled.sum(axis=1) == np.minimum(load, cap)).all()   # an expert holds min(load, cap) tokens
+    per_token = np.bincount(I[filled], minlength=n)
+    assert per_token.max() <= m
+    for i in range(e):                                           # a token sits at most once in a buffer
+        assert len(set(I[i][filled[i]].tolist())) == filled[i].sum()
+    # priority: second choices never displace first choices.  Expert 0 is every token's second choice
+    # except for the last `cap` tokens, whose first choice it is: those must all be placed.
+    n, cap = 30, 5
+    S = np.zeros((n, 3), dtype=np.float32)
+    S[:, 0], S[:, 1], S[:, 2] = 0.3, 0.6, 0.1
+    S[n - cap:, 0], S[n - cap:, 1] = 0.6, 0.3
+    _, I, load = ref.token_choice(S, 2, cap)
+    assert I[0].tolist() == list(range(n - cap, n)) and load[0] == n
+
+
+def test_token_choice_layer_without_drops_is_dense_top_m_mixture():
+    # buffers as large as the batch: nothing is dropped, X_out[l] = sum over l's top-m experts of S[l,i] FFN_i(x_l)
+    w = wl.scaled(wl.WORKLOADS["cfg1"], n=24, d=8, e=4, d_ff=12, act=wl.ACT_GELU, seed=9)
+    inp = wl.make_inputs(w)
+    m = 2
+    out = ref.forward_token_choice(inp["X"], inp["Wg"], inp["W1"], inp["W2"], c=float(w.e), m=m, act=w.act)
+    assert out["cap"] == w.n and (out["load"] <= w.n).all()
+    S = out["S"].astype(np.float64)
+    X = inp["X"].astype(np.float64)
+    expect = np.zeros((w.n, w.d))
+    for l in range(w.n):
+        top = np.argsort(-out["S"][l], kind="stable")[:m]
+        for i in top:
+            a = X[l] @ inp["W1"][i].astype(np.float64)
+            h = np.array([0.5 * t * (1.0 + math.erf(t / math.sqrt(2.0))) for t in a])
+            expect[l] += S[l, i] * (h @ inp["W2"][i].astype(np.float64))
+    np.testing.assert_allclose(out["X_out"], expect, rtol=1e-12, atol=1e-14)
+    # identity experts, m = e: every token keeps the whole of itself (the scores sum to 1)
+    out = ref.forward_token_choice(inp["X"], inp["Wg"], None, None, c=float(w.e), m=w.e, act=wl.ACT_IDENTITY)
+    np.testing.assert_allclose(out["X_out"], X * S.sum(axis=1, keepdims=True), rtol=1e-12)
+    # m = e with full buffers routes every token to every expert, like expert choice at c = e
+    ec = ref.forward(inp["X"], inp["Wg"], inp["W1"], inp["W2"], c=float(w.e), act=w.act)
+    tc = ref.forward_token_choice(inp["X"], inp["Wg"], inp["W1"], inp["W2"], c=float(w.e), m=w.e, act=w.act)
+    np.testing.assert_allclose(tc["X_out"], ec["X_out"], rtol=1e-12, atol=1e-14)
+
+
 def test_workload_generators_are_seeded_and_shaped():
     w = wl.WORKLOADS["cfg1"]
     a, b = wl.make_inputs(w), wl.make_inputs(w)
