@@ -43,6 +43,9 @@ def parse_args():
                     help="cfg2 (headline), cfg3, cfg5 (routing only), cfg4 (forward + backward)")
     ap.add_argument("--groups", type=int, default=1,
                     help="expert choice inside this many equal runs of tokens (1: the paper's global TopK)")
+    ap.add_argument("--token-choice", type=int, default=0, metavar="M",
+                    help="route with the token-choice baseline of Sec. 3.1 instead (every token's top-M experts, "
+                         "buffers of floor(n*c/e) rows, dropping); reports the load imbalance as well")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--copy-calibration", type=int, default=0, metavar="MiB",
                     help="only run a plain device-to-device copy of this many MiB five times (reference "
@@ -84,6 +87,10 @@ def main() -> int:
     if groups < 1 or n % groups != 0 or (groups > 1 and w.backward):
         print("bench.py: --groups must divide the token count (forward workloads only)", file=sys.stderr)
         return 2
+    tc = args.token_choice
+    if tc and (groups > 1 or w.backward or not (1 <= tc <= min(e, 8))):
+        print("bench.py: --token-choice M needs a forward workload, one group and 1 <= M <= min(e, 8)", file=sys.stderr)
+        return 2
     k_g = m.ec_moe_capacity(n // groups, e, w.c)
     k = groups * k_g          # rows of an expert's bucket (groups = 1: Eq. 1)
     b = 2 if w.dtype == wl.DTYPE_BF16 else 4
@@ -123,7 +130,9 @@ def main() -> int:
                               gr["dX"], gr["dWg"], gr["dW1"], gr["dW2"], w.act, ws)
     else:
         def step():
-            if groups == 1:
+            if tc:
+                m.ec_moe_forward_token_choice(X, Wg, W1, W2, w.c, tc, Xout, w.act, ws)
+            elif groups == 1:
                 m.ec_moe_forward(X, Wg, W1, W2, w.c, Xout, w.act, ws)
             else:
                 m.ec_moe_forward_grouped(X, Wg, W1, W2, w.c, groups, Xout, w.act, ws)
@@ -146,11 +155,16 @@ def main() -> int:
     Xe = torch.empty((e, k, d), dtype=dt, device="cuda") if d_ff else Xin
     names = ["gate", "topk", "dispatch"] + (["expert_ffn"] if d_ff else []) + ["combine"]
 
+    Sn = torch.empty((n, e), dtype=torch.float32, device="cuda") if tc else None
+    load = torch.empty((e,), dtype=torch.int32, device="cuda") if tc else None
+
     def staged_step(events):
         events[0].record()
-        m.ec_moe_gate(X, Wg, None, St, ws)
+        m.ec_moe_gate(X, Wg, Sn, None if tc else St, ws)
         events[1].record()
-        if groups == 1:
+        if tc:
+            m.ec_moe_token_choice(Sn, tc, k, G, I, load, ws)
+        elif groups == 1:
             m.ec_moe_topk_tokens(St, k, G, I, ws)
         else:
             m.ec_moe_topk_tokens_grouped(St, groups, k_g, G, I, ws)
@@ -229,8 +243,12 @@ def main() -> int:
         se = e if d_ff == 0 else max(1, min(e, int(8 * (1024 * 768 * 3072) / max(1, k * d * d_ff))))
         t0 = time.perf_counter()
         S_o = ref.gate(inp["X"], inp["Wg"])
-        G_o, I_o = ref.topk_tokens(S_o, k) if groups == 1 else ref.topk_tokens_grouped(S_o, k_g, groups)
-        Xin_o = ref.dispatch(inp["X"], I_o)
+        if tc:
+            G_o, I_o, _ = ref.token_choice(S_o, tc, k)
+            Xin_o = ref.dispatch_padded(inp["X"], I_o)
+        else:
+            G_o, I_o = ref.topk_tokens(S_o, k) if groups == 1 else ref.topk_tokens_grouped(S_o, k_g, groups)
+            Xin_o = ref.dispatch(inp["X"], I_o)
         t_route = time.perf_counter() - t0
         t_ffn = 0.0
         if d_ff:
@@ -241,7 +259,7 @@ def main() -> int:
         else:
             Xe_o = Xin_o
         t0 = time.perf_counter()
-        ref.combine(Xe_o, G_o, I_o, n)
+        (ref.combine_padded if tc else ref.combine)(Xe_o, G_o, I_o, n)
         t_comb = time.perf_counter() - t0
         total = t_route + t_ffn + t_comb
         cpu_baseline = {"value": round(n / total, 1), "unit": "tokens/s", "cores": int(threads), "kind": "oracle",
@@ -256,10 +274,19 @@ def main() -> int:
         "dtype": "bf16" if w.dtype == wl.DTYPE_BF16 else "f32", "data": "synthetic",
         "config": {"workload": f"{w.name}: EC-MoE layer forward{' + backward' if w.backward else ''}, "
                                f"n={n} d={d} e={e} c={w.c:g} k={k} d_ff={d_ff}"
-                               + (f", TopK inside {groups} groups of {n // groups} tokens" if groups > 1 else ""),
+                               + (f", TopK inside {groups} groups of {n // groups} tokens" if groups > 1 else "")
+                               + (f", token-choice top-{tc} routing with dropping (baseline)" if tc else ""),
                    "act": {0: "relu", 1: "gelu", 2: "identity"}[w.act], "seed": w.seed},
         "roofline": roofline, "cpu_baseline": cpu_baseline, "stages": stages,
     }
+    if tc:
+        # the load imbalance Sec. 3.1 describes, on this synthetic gate: tokens per expert before dropping
+        ld = load.cpu().numpy().astype(np.int64)
+        placed = int((I.cpu().numpy() >= 0).sum())
+        out["routing"] = {"kind": f"token-choice top-{tc}", "buffer_rows": int(k),
+                          "max_over_capacity_ratio": round(float(ld.max()) / k - 1.0, 4),
+                          "dropped_fraction": round(1.0 - placed / float(n * tc), 4),
+                          "empty_buffer_rows": int(e * k - placed)}
     print(json.dumps(out), flush=True)
     return 0
 

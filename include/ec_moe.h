@@ -98,7 +98,8 @@ int ec_moe_topk_tokens_grouped(const float* St, int64_t n, int64_t e, int64_t gr
 
 /* Sec. 3.2, Eq. 3 (first line), the "shuffle" stage of Sec. 3.4:
  * X_in[i,j,:] = X[I[i,j],:].  X [n,d], X_in [e,k,d] in `dtype`; a bit-exact
- * copy.  Every I[i,j] must lie in [0,n) (not checked on the device). */
+ * copy.  Every I[i,j] must lie in [0,n) (not checked on the device), or be -1: an empty row
+ * (token-choice routing), which is filled with zeros. */
 int ec_moe_dispatch(const void* X, const int32_t* I, void* Xin,
                     int64_t n, int64_t d, int64_t e, int64_t k, int dtype, void* stream);
 
@@ -119,7 +120,7 @@ int ec_moe_expert_ffn(const void* Xin, const void* W1, const void* W2, void* Xe,
  * for tokens no expert selected.  Deterministic: a token's contributions are
  * added in ascending expert order in fp32 and rounded once to `dtype`; no
  * floating-point atomics.  A token may appear at most once per expert (true of
- * any TopK output) and every I[i,j] must lie in [0,n).
+ * any TopK output) and every I[i,j] must lie in [0,n) or be -1 (empty row, skipped).
  * X_e [e,k,d], G [e,k], I [e,k], X_out [n,d].  e <= EC_MOE_MAX_EXPERTS. */
 int ec_moe_combine(const void* Xe, const float* G, const int32_t* I, void* Xout,
                    int64_t n, int64_t d, int64_t e, int64_t k, int dtype,
@@ -147,6 +148,31 @@ int ec_moe_forward_grouped(const void* X, const void* Wg, const void* W1, const 
                            void* Xin_out, void* A_out, void* H_out, void* Xe_out,
                            int64_t n, int64_t d, int64_t e, int64_t d_ff, int act, int dtype,
                            void* ws, size_t ws_bytes, void* stream);
+
+/* Sec. 3.1: conventional token-choice routing, the baseline the paper argues against.  Every token
+ * independently takes its m best experts of S[l,:] (m = 1: Switch Transformer, m = 2: GShard;
+ * Sec. 3.4), ties to the lower expert index.  An expert's buffer has `cap` rows; all first
+ * choices are placed before any second choice, ascending token index inside a rank of choice;
+ * a token that finds the buffer full is dropped there (the paper only says that an expert takes at
+ * most a maximum number of tokens; the placement order is this library's reading).
+ * S [n,e] float.  Outputs: I [e,cap] int32 token index or -1 for an empty row; G [e,cap] float
+ * = S[I[i,j], i] bit for bit, 0 in empty rows; load [e] int32 (optional) = tokens that chose the
+ * expert before dropping, so load/cap - 1 is the over-capacity ratio of Sec. 3.1.
+ * ec_moe_dispatch and ec_moe_combine accept such I: an empty row gathers zeros and adds nothing.
+ * 1 <= m <= min(e, 8), 1 <= cap <= n.  ws: at least 32*n bytes. */
+int ec_moe_token_choice(const float* S, int64_t n, int64_t e, int64_t m, int64_t cap,
+                        float* G, int32_t* I, int32_t* load, void* ws, size_t ws_bytes, void* stream);
+
+/* The layer of Eq. 3-4 behind token-choice routing: gate (Eq. 2, first line), ec_moe_token_choice
+ * with cap = floor(n*c/e) (Eq. 1: with c = m the buffers match expert choice at equal cost, the
+ * comparison of Sec. 3.4), dispatch, expert FFN, combine with the raw scores as weights.
+ * Optional outputs, NULL to skip: S_out [n,e], G_out / I_out [e,cap], load_out [e],
+ * Xin_out / Xe_out [e,cap,d].  Workspace: ec_moe_workspace_bytes with k = cap.  Forward only. */
+int ec_moe_forward_token_choice(const void* X, const void* Wg, const void* W1, const void* W2,
+                                double c, int64_t m, void* Xout, float* S_out, float* G_out,
+                                int32_t* I_out, int32_t* load_out, void* Xin_out, void* Xe_out,
+                                int64_t n, int64_t d, int64_t e, int64_t d_ff, int act, int dtype,
+                                void* ws, size_t ws_bytes, void* stream);
 
 /* Gradient of <dY, X_out> through Eq. 2-4 with the selection I held constant
  * and the gate values G differentiable (Sec. 3.4: the gating network is

@@ -33,6 +33,7 @@ WsLayout ws_layout(int64_t n, int64_t d, int64_t e, int64_t k, int64_t d_ff, int
     L.slot_cnt = take((size_t)n * 4);
     L.slots = take((size_t)n * COMBINE_SLOT_CAP * 4);
     L.sortkeys = take(topk_ws_bytes(n, e, k));
+    L.choice = take((size_t)n * 8 * 4);
     L.bwd = off;
     if (with_backward) take(bwd_ws_bytes(n, d, e, k, d_ff, dtype));
     L.total = off;
@@ -231,6 +232,65 @@ int ec_moe_forward_grouped(const void* X, const void* Wg, const void* W1, const 
                            int dtype, void* ws, size_t ws_bytes, void* stream) {
     return forward_impl(X, Wg, W1, W2, c, groups, Xout, S_out, G_out, I_out, Xin_out, A_out, H_out, Xe_out, n, d, e,
                         d_ff, act, dtype, ws, ws_bytes, stream);
+}
+
+int ec_moe_token_choice(const float* S, int64_t n, int64_t e, int64_t m, int64_t cap, float* G, int32_t* I,
+                        int32_t* load, void* ws, size_t ws_bytes, void* stream) {
+    if (!S || !G || !I || n <= 0 || e <= 0 || e > EC_MOE_MAX_EXPERTS || n >= (int64_t)1 << 31 || m < 1 || m > e ||
+        m > 8 || cap < 1 || cap > n || e * cap >= (int64_t)1 << 31 || !all_aligned(S, G, I, load))
+        return EC_ERR_INVALID_ARG;
+    if (!ws_ok(ws, ws_bytes, (size_t)n * 8 * 4)) return EC_ERR_WORKSPACE;
+    return launch_token_choice(S, n, e, m, cap, G, I, load, (int32_t*)ws, nullptr, nullptr, 0, nullptr,
+                               (hipStream_t)stream);
+}
+
+int ec_moe_forward_token_choice(const void* X, const void* Wg, const void* W1, const void* W2, double c, int64_t m,
+                                void* Xout, float* S_out, float* G_out, int32_t* I_out, int32_t* load_out,
+                                void* Xin_out, void* Xe_out, int64_t n, int64_t d, int64_t e, int64_t d_ff, int act,
+                                int dtype, void* ws, size_t ws_bytes, void* stream) {
+    int64_t k = 0;  // rows of an expert's buffer
+    if (ec_moe_capacity(n, e, c, &k) != EC_OK || m < 1 || m > e || m > 8) return EC_ERR_INVALID_ARG;
+    const bool identity = (W1 == nullptr && W2 == nullptr);
+    if (!X || !Wg || !Xout || !sizes_ok(n, d, e, k) || !dtype_ok(dtype) || !act_ok(act) || !width_ok(d, dtype) ||
+        !all_aligned(X, Wg, W1, W2, Xout, S_out, G_out, I_out, load_out, Xin_out, Xe_out))
+        return EC_ERR_INVALID_ARG;
+    if (identity) {
+        if (act != EC_ACT_IDENTITY) return EC_ERR_INVALID_ARG;
+        d_ff = 0;
+    } else {
+        if (!W1 || !W2 || d_ff <= 0 || d_ff >= (int64_t)1 << 31 || !width_ok(d_ff, dtype))
+            return EC_ERR_INVALID_ARG;
+    }
+    const WsLayout L = ws_layout(n, d, e, k, d_ff, dtype, 0);
+    if (!ws_ok(ws, ws_bytes, L.total)) return EC_ERR_WORKSPACE;
+    hipStream_t st = (hipStream_t)stream;
+
+    float* S = S_out ? S_out : (float*)at(ws, L.st);  // [n, e]: the same size as the S^T region
+    float* G = G_out ? G_out : (float*)at(ws, L.g);
+    int32_t* I = I_out ? I_out : (int32_t*)at(ws, L.i);
+    void* Xin = Xin_out ? Xin_out : at(ws, L.xin);
+
+    const CombineIndex ix = combine_index_at(ws, L, e);
+    int rc = launch_gate(X, Wg, S, nullptr, n, d, e, dtype, combine_zero_ptr(ix), combine_zero_words(ix, n, e), st);
+    if (rc != EC_OK) return rc;
+    rc = launch_token_choice(S, n, e, m, k, G, I, load_out, (int32_t*)at(ws, L.choice),
+                             ix.use_slots ? ix.slot_cnt : nullptr, ix.slots, ix.slot_cap,
+                             ix.use_slots ? nullptr : ix.bitmap, st);
+    if (rc != EC_OK) return rc;
+    const bool fused_gather = !identity && Xin_out == nullptr && ffn_can_gather(dtype, n, k, d, d_ff);
+    if (!fused_gather) {
+        rc = launch_dispatch(X, I, Xin, n, d, e, k, dtype, st);
+        if (rc != EC_OK) return rc;
+    }
+    const void* Xe = Xin;
+    if (!identity) {
+        void* Xe_w = Xe_out ? Xe_out : at(ws, L.xe);
+        rc = launch_ffn(fused_gather ? nullptr : Xin, X, I, n, W1, W2, Xe_w, nullptr, at(ws, L.h), e, k, d, d_ff, act,
+                        dtype, st);
+        if (rc != EC_OK) return rc;
+        Xe = Xe_w;
+    }
+    return launch_combine(Xe, G, I, Xout, n, d, e, k, dtype, ix, st);
 }
 
 int ec_moe_backward(const void* dY, const void* X, const void* Wg, const void* W1, const void* W2, const float* S,

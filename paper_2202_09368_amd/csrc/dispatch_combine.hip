@@ -1,6 +1,6 @@
 // Dispatch ("shuffle", Sec. 3.2 Eq. 3 first line) and combine ("unshuffle", Eq. 4).
 //
-// dispatch: X_in[i,j,:] = X[I[i,j],:] -- a row gather with 16-byte lanes.
+// dispatch: X_in[i,j,:] = X[I[i,j],:] -- a row gather with 16-byte lanes (I = -1: a row of zeros).
 // combine:  X_out[l,:] = sum_{(i,j): I[i,j]=l} G[i,j] X_e[i,j,:], deterministic.
 //   A token-major index is built from I with integer atomics only (see below); one group of
 //   lanes per token then adds that token's bucket rows in ascending expert order in fp32.
@@ -17,9 +17,10 @@ dispatch_kernel(const uint4* __restrict__ X, const int32_t* __restrict__ I, uint
     const int sub = threadIdx.x / tpr, t = threadIdx.x % tpr;
     for (long long r = (long long)blockIdx.x * rows_per_block + sub; r < rows;
          r += (long long)gridDim.x * rows_per_block) {
-        const uint4* src = X + (size_t)I[r] * vec_per_row;
+        const int tok = I[r];  // -1: an empty buffer row (token-choice routing), filled with zeros
+        const uint4* src = X + (size_t)(tok < 0 ? 0 : tok) * vec_per_row;
         uint4* dst = Xin + (size_t)r * vec_per_row;
-        for (int v = t; v < vec_per_row; v += tpr) dst[v] = src[v];
+        for (int v = t; v < vec_per_row; v += tpr) dst[v] = tok < 0 ? make_uint4(0u, 0u, 0u, 0u) : src[v];
     }
 }
 
@@ -29,9 +30,10 @@ dispatch_scalar_kernel(const float* __restrict__ X, const int32_t* __restrict__ 
                        long long rows, int d) {
     const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
     for (long long r = (long long)blockIdx.x * 4 + wave; r < rows; r += (long long)gridDim.x * 4) {
-        const float* src = X + (size_t)I[r] * d;
+        const int tok = I[r];
+        const float* src = X + (size_t)(tok < 0 ? 0 : tok) * d;
         float* dst = Xin + (size_t)r * d;
-        for (int v = lane; v < d; v += kWave) dst[v] = src[v];
+        for (int v = lane; v < d; v += kWave) dst[v] = tok < 0 ? 0.0f : src[v];
     }
 }
 
@@ -79,7 +81,7 @@ __global__ void __launch_bounds__(256)
 bitmap_kernel(const int32_t* __restrict__ I, uint32_t* __restrict__ bitmap, long long rows, int k, int words) {
     for (long long r = (long long)blockIdx.x * 256 + threadIdx.x; r < rows; r += (long long)gridDim.x * 256) {
         int i = (int)(r / k);
-        atomicOr(&bitmap[(size_t)I[r] * words + (i >> 5)], 1u << (i & 31));
+        if (I[r] >= 0) atomicOr(&bitmap[(size_t)I[r] * words + (i >> 5)], 1u << (i & 31));  // -1: empty row
     }
 }
 
@@ -88,6 +90,7 @@ slots_kernel(const int32_t* __restrict__ I, int32_t* __restrict__ slot_cnt, int3
              long long rows, int cap) {
     for (long long r = (long long)blockIdx.x * 256 + threadIdx.x; r < rows; r += (long long)gridDim.x * 256) {
         const int l = I[r];
+        if (l < 0) continue;  // empty buffer row
         const int s = atomicAdd(&slot_cnt[l], 1);
         if (s < cap) slots[(size_t)l * cap + s] = (int32_t)r;
     }
@@ -168,6 +171,7 @@ inverse_index_kernel(const int32_t* __restrict__ I, const uint32_t* __restrict__
     for (long long r = (long long)blockIdx.x * 256 + threadIdx.x; r < rows; r += (long long)gridDim.x * 256) {
         int i = (int)(r / k);
         int l = I[r];
+        if (l < 0) continue;  // empty buffer row
         const uint32_t* bm = bitmap + (size_t)l * words;
         int rank = 0;
         for (int w = 0; w < (i >> 5); ++w) rank += __popc(bm[w]);

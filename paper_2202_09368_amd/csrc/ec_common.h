@@ -55,6 +55,7 @@ struct WsLayout {
     size_t slot_cnt;   // int32 [n]: experts that chose a token                     (slot form, e <= COMBINE_SLOT_CAP)
     size_t slots;      // int32 [n, COMBINE_SLOT_CAP]: their bucket rows, arrival order
     size_t sortkeys;   // uint64 [e, pow2(k)]: top-k sort staging when a bucket exceeds LDS
+    size_t choice;     // int32 [8, n]: every token's chosen experts, rank-major (token-choice routing)
     size_t bwd;        // start of the backward-only region
     size_t total;
 };
@@ -90,6 +91,9 @@ int launch_gate(const void* X, const void* Wg, float* S, float* St, int64_t n, i
 int launch_topk(const float* St, int64_t n, int64_t e, int64_t k, float* G, int32_t* I,
                 unsigned long long* sortkeys_ws, int32_t* slot_cnt, int32_t* slots, int slot_cap, uint32_t* bitmap,
                 hipStream_t stream, int64_t groups = 1);
+int launch_token_choice(const float* S, int64_t n, int64_t e, int64_t m, int64_t cap, float* G, int32_t* I,
+                        int32_t* load, int32_t* choice_ws, int32_t* slot_cnt, int32_t* slots, int slot_cap,
+                        uint32_t* bitmap, hipStream_t stream);
 int launch_combine_index(const int32_t* I, int64_t n, int64_t e, int64_t k, const CombineIndex& ix,
                          hipStream_t stream);
 int launch_dispatch(const void* X, const int32_t* I, void* Xin, int64_t n, int64_t d, int64_t e, int64_t k,

@@ -149,8 +149,9 @@ gemm_bf16_kernel(const bf16_t* __restrict__ Aall, const bf16_t* __restrict__ Bal
         } else {
             const int row = c >> 3, kch = c & 7;
             if (gather != nullptr) {
-                const int gm = m0 + row;  // rows past M point outside the buffer: they load zeros
-                a_voff[r] = gm < M ? (gather[(size_t)g * M + gm] * K + kch * 8) * 2 : 0x7FFFFF00;
+                const int gm = m0 + row;  // rows past M and empty rows (index -1) point outside the buffer: zeros
+                const int src = gm < M ? gather[(size_t)g * M + gm] : -1;
+                a_voff[r] = src >= 0 ? (src * K + kch * 8) * 2 : 0x7FFFFF00;
             } else {
                 a_voff[r] = ((m0 + row) * K + kch * 8) * 2;
             }

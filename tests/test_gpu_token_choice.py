@@ -1,0 +1,138 @@
+"""GPU parity for the token-choice baseline (Sec. 3.1 of the paper): routing bit for bit against the
+oracle on the same scores, empty buffer rows through dispatch and combine, and the whole layer."""
+import numpy as np
+import pytest
+import torch
+
+import workloads as wl
+from gpu_util import max_rel_err, max_rel_err_rows, out_tol, score_tolerance, to_dev, to_host, torch_dtype
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def m():
+    if not torch.cuda.is_available():
+        pytest.skip("no GPU")
+    import paper_2202_09368_amd as mod
+    mod.lib()
+    return mod
+
+
+@pytest.fixture(scope="module")
+def ref():
+    from oracle import ec_moe_ref
+    return ec_moe_ref
+
+
+def _p(msg):
+    print(msg, flush=True)
+
+
+def _scores(kind, n, e, seed):
+    r = np.random.default_rng(seed)
+    if kind == "softmax":      # peaked rows: a few experts attract most tokens
+        z = r.standard_normal((n, e)) * 2.0 + np.linspace(1.5, -1.5, e)[None, :]
+        p = np.exp(z - z.max(axis=1, keepdims=True))
+        return (p / p.sum(axis=1, keepdims=True)).astype(np.float32)
+    if kind == "levels":       # many exact ties between experts
+        return (np.floor(r.random((n, e)) * 3) / 3).astype(np.float32)
+    if kind == "const":
+        return np.full((n, e), 1.0 / e, np.float32)
+    return r.random((n, e), dtype=np.float32)
+
+
+@pytest.mark.parametrize("n,e,m_top,cap,kind", [
+    (1, 1, 1, 1, "rand"), (7, 3, 2, 2, "rand"), (1000, 4, 1, 250, "rand"), (1000, 4, 2, 500, "softmax"),
+    (5003, 16, 2, 625, "softmax"), (4096, 64, 2, 128, "softmax"), (4096, 64, 1, 64, "levels"),
+    (3000, 8, 8, 3000, "rand"),                 # m = e, buffers as large as the batch: nothing dropped
+    (3000, 5, 2, 10, "const"),                  # every token picks experts 0 and 1: 2 full buffers, 3 empty
+    (70000, 3, 2, 20000, "softmax"), (20000, 300, 3, 100, "rand"),
+])
+def test_token_choice_routing(m, ref, n, e, m_top, cap, kind):
+    _p(f"[token choice] n={n} e={e} m={m_top} cap={cap} {kind}")
+    S_h = _scores(kind, n, e, n + e + cap)
+    S = to_dev(S_h)
+    G = torch.empty((e, cap), dtype=torch.float32, device="cuda")
+    I = torch.empty((e, cap), dtype=torch.int32, device="cuda")
+    load = torch.empty((e,), dtype=torch.int32, device="cuda")
+    ws = torch.empty(32 * n + 256, dtype=torch.uint8, device="cuda")
+    m.ec_moe_token_choice(S, m_top, cap, G, I, load, ws)
+    torch.cuda.synchronize()
+    G_o, I_o, load_o = ref.token_choice(S_h, m_top, cap)
+    assert (to_host(load) == load_o).all()
+    assert (to_host(I) == I_o).all()
+    assert (to_host(G).view(np.uint32) == G_o.view(np.uint32)).all()
+
+
+def test_dispatch_and_combine_with_empty_rows(m, ref):
+    n, d, e, cap = 600, 64, 24, 40
+    r = np.random.default_rng(3)
+    S_h = _scores("softmax", n, e, 17)
+    G_h, I_h, _ = ref.token_choice(S_h, 2, cap)
+    assert (I_h < 0).any() and (I_h >= 0).any()
+    for dtype in (np.float32, "bf16"):
+        X_h = r.standard_normal((n, d)).astype(np.float32)
+        Xe_h = r.standard_normal((e, cap, d)).astype(np.float32)
+        if dtype == "bf16":
+            X_h, Xe_h = wl.f32_to_bf16_bits(X_h), wl.f32_to_bf16_bits(Xe_h)
+        X, Xe, G, I = to_dev(X_h), to_dev(Xe_h), to_dev(G_h), to_dev(I_h)
+        Xin = torch.empty((e, cap, d), dtype=X.dtype, device="cuda")
+        m.ec_moe_dispatch(X, I, Xin)
+        code = wl.DTYPE_BF16 if dtype == "bf16" else wl.DTYPE_F32
+        ws = m.alloc_workspace(n, d, e, cap, 0, code)
+        Xout = torch.empty((n, d), dtype=X.dtype, device="cuda")
+        m.ec_moe_combine(Xe, G, I, Xout, ws)
+        torch.cuda.synchronize()
+        assert (to_host(Xin) == ref.dispatch_padded(X_h, I_h)).all()
+        tol = 2e-2 if dtype == "bf16" else 1e-5
+        assert max_rel_err(to_host(Xout), ref.combine_padded(Xe_h, G_h, I_h, n)) <= tol
+
+
+@pytest.mark.parametrize("base,kw,m_top,c", [
+    ("cfg1", dict(n=512, d=64, e=8, d_ff=128), 2, 2.0),                 # fp32
+    ("cfg2", dict(n=4096, d=256, e=16, d_ff=512), 2, 2.0),              # bf16, fused gather, slot lists
+    ("cfg2", dict(n=4096, d=256, e=16, d_ff=512), 1, 1.0),
+    ("cfg3", dict(n=4096, d=128, e=64, d_ff=256), 2, 2.0),              # bf16, CSR combine index
+    ("cfg5", dict(n=8192, d=128, e=32), 2, 2.0),                        # identity experts, skewed tokens
+])
+def test_token_choice_forward(m, ref, base, kw, m_top, c):
+    w = wl.scaled(wl.WORKLOADS[base], c=c, **kw)
+    inp = wl.make_inputs(w)
+    n, d, e = w.n, w.d, w.e
+    cap = ref.capacity(n, c, e)
+    _p(f"[token choice forward] {base} n={n} d={d} e={e} m={m_top} cap={cap}")
+    dt = torch_dtype(w)
+    ws = m.alloc_workspace(n, d, e, cap, w.d_ff, w.dtype)
+    t = {key: to_dev(inp[key]) for key in ("X", "Wg", "W1", "W2") if key in inp}
+    Xout = torch.empty((n, d), dtype=dt, device="cuda")
+    S = torch.empty((n, e), dtype=torch.float32, device="cuda")
+    G = torch.empty((e, cap), dtype=torch.float32, device="cuda")
+    I = torch.empty((e, cap), dtype=torch.int32, device="cuda")
+    load = torch.empty((e,), dtype=torch.int32, device="cuda")
+    Xe = torch.empty((e, cap, d), dtype=dt, device="cuda") if w.d_ff else None
+    m.ec_moe_forward_token_choice(t["X"], t["Wg"], t.get("W1"), t.get("W2"), c, m_top, Xout, w.act, ws,
+                                  S_out=S, G_out=G, I_out=I, load_out=load, Xe_out=Xe)
+    torch.cuda.synchronize()
+    S_h, G_h, I_h = to_host(S), to_host(G), to_host(I)
+    S_ref = ref.gate(inp["X"], inp["Wg"])
+    assert (max_rel_err_rows(S_h, S_ref) <= score_tolerance(inp["X"], inp["Wg"])).all()
+    G_o, I_o, load_o = ref.token_choice(S_h, m_top, cap)       # same scores: bit for bit
+    assert (I_h == I_o).all() and (G_h.view(np.uint32) == G_o.view(np.uint32)).all()
+    assert (to_host(load) == load_o).all()
+    dropped = int(load_o.sum() - (I_o >= 0).sum())
+    _p(f"[token choice forward] max load / cap = {load_o.max() / cap:.2f}, dropped {dropped} of {n * m_top} choices")
+    X_in = ref.dispatch_padded(inp["X"], I_h)
+    if w.d_ff:
+        Xe_ref = ref.expert_ffn(X_in, inp["W1"], inp["W2"], w.act)
+        assert max_rel_err(to_host(Xe), Xe_ref) <= out_tol(w)
+    else:
+        Xe_ref = ref.widen(X_in)
+    err = max_rel_err(to_host(Xout), ref.combine_padded(Xe_ref, G_h, I_h, n))
+    _p(f"[token choice forward] X_out max rel err {err:.3e}")
+    assert err <= out_tol(w)
+    # without the optional outputs (workspace buffers, fused gather) the result is the same
+    Xout2 = torch.empty_like(Xout)
+    m.ec_moe_forward_token_choice(t["X"], t["Wg"], t.get("W1"), t.get("W2"), c, m_top, Xout2, w.act, ws)
+    torch.cuda.synchronize()
+    assert (to_host(Xout2) == to_host(Xout)).all()
