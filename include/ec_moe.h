@@ -174,6 +174,30 @@ int ec_moe_forward_token_choice(const void* X, const void* Wg, const void* W1, c
                                 int64_t n, int64_t d, int64_t e, int64_t d_ff, int act, int dtype,
                                 void* ws, size_t ws_bytes, void* stream);
 
+/* Sec. 3.3: expert choice with at most b experts per token.  A [e,n] solves
+ *   max <S^T, A> + lambda H(A),  rows sum to k, columns sum to at most b, 0 <= A <= 1
+ * by Dykstra's algorithm over the three constraint sets (the paper: lambda = 0.001, at most 100
+ * iterations), and the buckets become TopK(A, k).  The paper prints neither the projections nor a
+ * stopping rule; this library's reading: KL projections (row scaling to k, column scaling by
+ * min(1, b / column sum), clipping at 1) with Dykstra's correction terms for the two inequality
+ * sets, in the log domain in float64, exactly `iters` sweeps (rows, columns, box).
+ * St [e,n] float scores; A [e,n] float output (rounded once at the end).  b > 0, lambda > 0,
+ * 0 <= iters <= 100000.  ws: ec_moe_capped_workspace_bytes(n, e).  2*iters + 2 launches. */
+size_t ec_moe_capped_workspace_bytes(int64_t n, int64_t e);
+int ec_moe_capped_assignment(const float* St, int64_t n, int64_t e, int64_t k, double b, double lambda,
+                             int64_t iters, float* A, void* ws, size_t ws_bytes, void* stream);
+
+/* ec_moe_forward with the routing of Sec. 3.3: I = indices of TopK(A, k) with A from
+ * ec_moe_capped_assignment on the layer's own scores; the gate weights stay G[i,j] = S[I[i,j], i]
+ * (the paper replaces only the indices).  Optional outputs, NULL to skip: S_out [n,e], G_out / I_out
+ * [e,k], A_out [e,n], Xe_out [e,k,d].  ws: ec_moe_workspace_bytes(n,d,e,k,d_ff,dtype,0)
+ * + ec_moe_capped_workspace_bytes(n,e) + 4*e*n rounded up to 256.  Forward only. */
+int ec_moe_forward_capped(const void* X, const void* Wg, const void* W1, const void* W2, double c,
+                          double b, double lambda, int64_t iters, void* Xout, float* S_out, float* G_out,
+                          int32_t* I_out, float* A_out, void* Xe_out,
+                          int64_t n, int64_t d, int64_t e, int64_t d_ff, int act, int dtype,
+                          void* ws, size_t ws_bytes, void* stream);
+
 /* Gradient of <dY, X_out> through Eq. 2-4 with the selection I held constant
  * and the gate values G differentiable (Sec. 3.4: the gating network is
  * trained through the top-k function).  Inputs: dY [n,d] and the forward's

@@ -38,7 +38,11 @@ degenerate routings, textbook dense FFN for e=1, finite differences and an
 autograd restatement for the backward; routing per group against the plain
 layer run on each group as a batch of its own and a brute-force selection;
 token-choice routing against a hand-worked example, a per-token brute force,
-the dense top-m mixture when nothing is dropped, and its priority rule).
+the dense top-m mixture when nothing is dropped, and its priority rule;
+the capped assignment of Sec. 3.3 against the linear programme solved by a
+library LP solver, the closed-form optimum when the cap is slack, and its
+constraints -- its projection formulas are a reading of the paper, which
+prints none: see the section's comment).
 """
 from __future__ import annotations
 
@@ -337,6 +341,73 @@ def forward_token_choice(X, Wg, W1, W2, c: float, m: int, act: int) -> Dict[str,
         X_e = expert_ffn(X_in, W1, W2, act)
     X_out = combine_padded(X_e, G, I, n)
     return {"cap": cap, "S": S, "G": G, "I": I, "load": load, "X_in": X_in, "X_e": X_e, "X_out": X_out}
+
+
+# ------------------------------------ expert choice with a cap per token ---
+# Sec. 3.3: limit the number of experts a token can get.  A[e,n] >= 0 solves the entropy-regularised
+# linear programme
+#     max <S^T, A> + lambda H(A),   H(A) = -sum A log A,
+#     rows sum to k,  columns sum to at most b,  0 <= A <= 1,
+# by Dykstra's algorithm, projecting in turn on the three constraint sets (lambda = 0.001, at most
+# 100 iterations), and the buckets are TopK(A, k) instead of TopK(S^T, k).  The paper gives neither
+# the projections nor a stopping rule.  Reading taken here: since <S^T,A> + lambda H(A) equals
+# -lambda KL(A || exp(S^T/lambda)) up to terms fixed by the row sums, the solution is the KL
+# projection of the Gibbs kernel exp(S^T/lambda) on the intersection, and Dykstra's algorithm is run
+# with KL projections (iterative Bregman projections), which are scalings:
+#   rows sum to k      A[i,:] *= k / sum_j A[i,j]                      (affine set: no correction)
+#   columns at most b  A[:,j] *= min(1, b / sum_i A[i,j])              (correction q_col[j])
+#   entries at most 1  A = min(A, 1)                                   (correction q_box[i,j])
+# with the usual Dykstra corrections for the two inequality sets (multiply the correction in before
+# projecting, keep input/output as the new correction).  All in the log domain, float64, because
+# exp(S/lambda) overflows.  A fixed number of sweeps is run (`iters`, the paper's maximum 100 by
+# default), each sweep = rows, columns, box in this order.  Gate weights stay the scores:
+# G[i,j] = S[I[i,j], i] (Sec. 3.3 replaces only the indices).
+def _logsumexp(a: np.ndarray, axis: int) -> np.ndarray:
+    m = a.max(axis=axis, keepdims=True)
+    return (m + np.log(np.exp(a - m).sum(axis=axis, keepdims=True))).squeeze(axis)
+
+
+def capped_assignment(S: np.ndarray, k: int, b: float, lam: float = 1e-3, iters: int = 100,
+                      out_dtype=np.float32) -> np.ndarray:
+    """A[e,n] of Sec. 3.3 after `iters` sweeps of rows / columns / box (float32 like S unless asked otherwise)."""
+    S = np.asarray(S)
+    n, e = S.shape
+    if not (1 <= k <= n) or not (b > 0) or not (lam > 0) or iters < 0:
+        raise ValueError("bad k, b, lambda or iteration count")
+    logA = S.T.astype(np.float64) / lam                 # log of the Gibbs kernel
+    lq_col = np.zeros(n)                                # log of the column set's correction (one scale per column)
+    lq_box = np.zeros((e, n))                           # log of the box set's correction
+    for _ in range(iters):
+        logA = logA + (math.log(k) - _logsumexp(logA, axis=1))[:, None]
+        B = logA + lq_col[None, :]
+        s = np.minimum(0.0, math.log(b) - _logsumexp(B, axis=0))
+        logA = B + s[None, :]
+        lq_col = -s
+        B = logA + lq_box
+        logA = np.minimum(B, 0.0)
+        lq_box = np.maximum(B, 0.0)
+    return np.exp(logA).astype(out_dtype)
+
+
+def forward_capped(X, Wg, W1, W2, c: float, act: int, b: float, lam: float = 1e-3,
+                   iters: int = 100) -> Dict[str, np.ndarray]:
+    """Eq. 1-4 with the routing indices taken from TopK(A, k) (Sec. 3.3), weights from S."""
+    n, d = np.asarray(X).shape
+    e = np.asarray(Wg).shape[1]
+    k = capacity(n, c, e)
+    S = gate(X, Wg)
+    A = capped_assignment(S, k, b, lam, iters)
+    _, I = topk_tokens(np.ascontiguousarray(A.T), k)
+    G = np.stack([S[I[i], i] for i in range(e)])
+    X_in = dispatch(X, I)
+    if W1 is None:
+        if act != ACT_IDENTITY:
+            raise ValueError("identity experts need act = ACT_IDENTITY")
+        X_e = widen(X_in)
+    else:
+        X_e = expert_ffn(X_in, W1, W2, act)
+    X_out = combine(X_e, G, I, n)
+    return {"k": k, "S": S, "A": A, "G": G, "I": I, "X_in": X_in, "X_e": X_e, "X_out": X_out}
 
 
 # ---------------------------------------------------------------- backward ---

@@ -52,6 +52,10 @@ _SIGNATURES = {
     "ec_moe_token_choice": (c_int, [_P, _I64, _I64, _I64, _I64, _P, _P, _P, _P, _SZ, _P]),
     "ec_moe_forward_token_choice": (c_int, [_P, _P, _P, _P, c_double, _I64, _P, _P, _P, _P, _P, _P, _P,
                                             _I64, _I64, _I64, _I64, c_int, c_int, _P, _SZ, _P]),
+    "ec_moe_capped_workspace_bytes": (c_size_t, [_I64, _I64]),
+    "ec_moe_capped_assignment": (c_int, [_P, _I64, _I64, _I64, c_double, c_double, _I64, _P, _P, _SZ, _P]),
+    "ec_moe_forward_capped": (c_int, [_P, _P, _P, _P, c_double, c_double, c_double, _I64, _P, _P, _P, _P, _P, _P,
+                                      _I64, _I64, _I64, _I64, c_int, c_int, _P, _SZ, _P]),
     "ec_moe_backward": (c_int, [_P] * 16 + [_I64] * 5 + [c_int, c_int, _P, _SZ, _P]),
     "ec_moe_last_hip_error": (c_int, []),
     "ec_moe_status_string": (c_char_p, [c_int]),
@@ -223,6 +227,30 @@ def ec_moe_forward_token_choice(X, Wg, W1, W2, c: float, m: int, Xout, act: int,
     _check("ec_moe_forward_token_choice", lib().ec_moe_forward_token_choice(
         _ptr(X), _ptr(Wg, dt), _ptr(W1, dt), _ptr(W2, dt), c, m, _ptr(Xout, dt), _ptr(S_out, torch.float32),
         _ptr(G_out, torch.float32), _ptr(I_out, torch.int32), _ptr(load_out, torch.int32), _ptr(Xin_out, dt),
+        _ptr(Xe_out, dt), n, d, e, d_ff, act, _dtype_code(X), wp, wb, _stream()))
+
+
+def ec_moe_capped_workspace_bytes(n: int, e: int) -> int:
+    return int(lib().ec_moe_capped_workspace_bytes(n, e))
+
+
+def ec_moe_capped_assignment(St, k: int, b: float, lam: float, iters: int, A, ws) -> None:
+    e, n = St.shape
+    wp, wb = _ws(ws)
+    _check("ec_moe_capped_assignment", lib().ec_moe_capped_assignment(
+        _ptr(St, torch.float32), n, e, k, b, lam, iters, _ptr(A, torch.float32), wp, wb, _stream()))
+
+
+def ec_moe_forward_capped(X, Wg, W1, W2, c: float, b: float, lam: float, iters: int, Xout, act: int, ws,
+                          S_out=None, G_out=None, I_out=None, A_out=None, Xe_out=None) -> None:
+    n, d = X.shape
+    e = Wg.shape[1]
+    d_ff = W1.shape[2] if W1 is not None else 0
+    wp, wb = _ws(ws)
+    dt = X.dtype
+    _check("ec_moe_forward_capped", lib().ec_moe_forward_capped(
+        _ptr(X), _ptr(Wg, dt), _ptr(W1, dt), _ptr(W2, dt), c, b, lam, iters, _ptr(Xout, dt),
+        _ptr(S_out, torch.float32), _ptr(G_out, torch.float32), _ptr(I_out, torch.int32), _ptr(A_out, torch.float32),
         _ptr(Xe_out, dt), n, d, e, d_ff, act, _dtype_code(X), wp, wb, _stream()))
 
 

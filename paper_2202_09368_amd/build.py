@@ -10,7 +10,7 @@ ROOT = os.path.dirname(PKG_DIR)
 CSRC = os.path.join(PKG_DIR, "csrc")
 LIB_PATH = os.path.join(PKG_DIR, "libec_moe.so")
 
-SOURCES = ["api.hip", "gate.hip", "topk.hip", "dispatch_combine.hip", "token_choice.hip", "ffn.hip", "backward.hip"]
+SOURCES = ["api.hip", "gate.hip", "topk.hip", "dispatch_combine.hip", "token_choice.hip", "capped.hip", "ffn.hip", "backward.hip"]
 
 # -packed-fp32-ops is switched off: hipcc must not form v_pk_*_f32 from float code.
 HIPCC_FLAGS = [

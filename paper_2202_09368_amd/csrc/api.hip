@@ -293,6 +293,80 @@ int ec_moe_forward_token_choice(const void* X, const void* Wg, const void* W1, c
     return launch_combine(Xe, G, I, Xout, n, d, e, k, dtype, ix, st);
 }
 
+size_t ec_moe_capped_workspace_bytes(int64_t n, int64_t e) {
+    if (n <= 0 || e <= 0 || e > EC_MOE_MAX_EXPERTS || n >= (int64_t)1 << 31) return 0;
+    return capped_ws_bytes(n, e);
+}
+
+static bool capped_args_ok(double b, double lambda, int64_t iters) {
+    return std::isfinite(b) && b > 0.0 && std::isfinite(lambda) && lambda > 0.0 && iters >= 0 && iters <= 100000;
+}
+
+int ec_moe_capped_assignment(const float* St, int64_t n, int64_t e, int64_t k, double b, double lambda,
+                             int64_t iters, float* A, void* ws, size_t ws_bytes, void* stream) {
+    if (!St || !A || !sizes_ok(n, 1, e, k) || !capped_args_ok(b, lambda, iters) || !all_aligned(St, A))
+        return EC_ERR_INVALID_ARG;
+    if (!ws_ok(ws, ws_bytes, capped_ws_bytes(n, e))) return EC_ERR_WORKSPACE;
+    return launch_capped_assignment(St, n, e, k, b, lambda, iters, A, ws, (hipStream_t)stream);
+}
+
+int ec_moe_forward_capped(const void* X, const void* Wg, const void* W1, const void* W2, double c, double b,
+                          double lambda, int64_t iters, void* Xout, float* S_out, float* G_out, int32_t* I_out,
+                          float* A_out, void* Xe_out, int64_t n, int64_t d, int64_t e, int64_t d_ff, int act,
+                          int dtype, void* ws, size_t ws_bytes, void* stream) {
+    int64_t k = 0;
+    if (ec_moe_capacity(n, e, c, &k) != EC_OK || !capped_args_ok(b, lambda, iters)) return EC_ERR_INVALID_ARG;
+    const bool identity = (W1 == nullptr && W2 == nullptr);
+    if (!X || !Wg || !Xout || !sizes_ok(n, d, e, k) || !dtype_ok(dtype) || !act_ok(act) || !width_ok(d, dtype) ||
+        !all_aligned(X, Wg, W1, W2, Xout, S_out, G_out, I_out, A_out, Xe_out))
+        return EC_ERR_INVALID_ARG;
+    if (identity) {
+        if (act != EC_ACT_IDENTITY) return EC_ERR_INVALID_ARG;
+        d_ff = 0;
+    } else {
+        if (!W1 || !W2 || d_ff <= 0 || d_ff >= (int64_t)1 << 31 || !width_ok(d_ff, dtype))
+            return EC_ERR_INVALID_ARG;
+    }
+    const WsLayout L = ws_layout(n, d, e, k, d_ff, dtype, 0);
+    // after the layer's own regions: the solver's state, then A when the caller does not want it
+    const size_t a_bytes = align_up((size_t)e * n * 4, 256);
+    if (!ws_ok(ws, ws_bytes, L.total + capped_ws_bytes(n, e) + a_bytes)) return EC_ERR_WORKSPACE;
+    hipStream_t st = (hipStream_t)stream;
+
+    float* St = (float*)at(ws, L.st);
+    float* G = G_out ? G_out : (float*)at(ws, L.g);
+    int32_t* I = I_out ? I_out : (int32_t*)at(ws, L.i);
+    void* Xin = at(ws, L.xin);
+    void* solver = at(ws, L.total);
+    float* A = A_out ? A_out : (float*)at(ws, L.total + capped_ws_bytes(n, e));
+
+    const CombineIndex ix = combine_index_at(ws, L, e);
+    int rc = launch_gate(X, Wg, S_out, St, n, d, e, dtype, combine_zero_ptr(ix), combine_zero_words(ix, n, e), st);
+    if (rc != EC_OK) return rc;
+    rc = launch_capped_assignment(St, n, e, k, b, lambda, iters, A, solver, st);
+    if (rc != EC_OK) return rc;
+    // indices from TopK(A, k); the values it returns are entries of A and are replaced by the scores
+    rc = launch_topk(A, n, e, k, G, I, nullptr, ix.use_slots ? ix.slot_cnt : nullptr, ix.slots, ix.slot_cap,
+                     ix.use_slots ? nullptr : ix.bitmap, st);
+    if (rc != EC_OK) return rc;
+    rc = launch_gather_scores(St, I, G, n, e, k, st);
+    if (rc != EC_OK) return rc;
+    const bool fused_gather = !identity && ffn_can_gather(dtype, n, k, d, d_ff);
+    if (!fused_gather) {
+        rc = launch_dispatch(X, I, Xin, n, d, e, k, dtype, st);
+        if (rc != EC_OK) return rc;
+    }
+    const void* Xe = Xin;
+    if (!identity) {
+        void* Xe_w = Xe_out ? Xe_out : at(ws, L.xe);
+        rc = launch_ffn(fused_gather ? nullptr : Xin, X, I, n, W1, W2, Xe_w, nullptr, at(ws, L.h), e, k, d, d_ff, act,
+                        dtype, st);
+        if (rc != EC_OK) return rc;
+        Xe = Xe_w;
+    }
+    return launch_combine(Xe, G, I, Xout, n, d, e, k, dtype, ix, st);
+}
+
 int ec_moe_backward(const void* dY, const void* X, const void* Wg, const void* W1, const void* W2, const float* S,
                     const float* G, const int32_t* I, const void* Xin, const void* A, const void* H,
                     const void* Xe, void* dX, float* dWg, float* dW1, float* dW2, int64_t n, int64_t d, int64_t e,

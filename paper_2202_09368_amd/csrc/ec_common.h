@@ -94,6 +94,11 @@ int launch_topk(const float* St, int64_t n, int64_t e, int64_t k, float* G, int3
 int launch_token_choice(const float* S, int64_t n, int64_t e, int64_t m, int64_t cap, float* G, int32_t* I,
                         int32_t* load, int32_t* choice_ws, int32_t* slot_cnt, int32_t* slots, int slot_cap,
                         uint32_t* bitmap, hipStream_t stream);
+size_t capped_ws_bytes(int64_t n, int64_t e);
+int launch_capped_assignment(const float* St, int64_t n, int64_t e, int64_t k, double b, double lambda,
+                             int64_t iters, float* A, void* ws, hipStream_t stream);
+int launch_gather_scores(const float* St, const int32_t* I, float* G, int64_t n, int64_t e, int64_t k,
+                         hipStream_t stream);
 int launch_combine_index(const int32_t* I, int64_t n, int64_t e, int64_t k, const CombineIndex& ix,
                          hipStream_t stream);
 int launch_dispatch(const void* X, const int32_t* I, void* Xin, int64_t n, int64_t d, int64_t e, int64_t k,

@@ -581,6 +581,86 @@ def test_token_choice_layer_without_drops_is_dense_top_m_mixture():
     np.testing.assert_allclose(tc["X_out"], ec["X_out"], rtol=1e-12, atol=1e-14)
 
 
+# ----------------------------------------- expert choice with a cap (Sec. 3.3) ---
+def _capped_lp(S, k, b):
+    """The linear programme of Sec. 3.3 without the entropy term, by a library LP solver."""
+    from scipy.optimize import linprog
+    n, e = S.shape
+    cost = -S.T.ravel().astype(np.float64)
+    rows = np.zeros((e, e * n))
+    for i in range(e):
+        rows[i, i * n:(i + 1) * n] = 1.0
+    cols = np.zeros((n, e * n))
+    for j in range(n):
+        cols[j, j::n] = 1.0
+    res = linprog(cost, A_ub=cols, b_ub=np.full(n, float(b)), A_eq=rows, b_eq=np.full(e, float(k)),
+                  bounds=(0.0, 1.0), method="highs")
+    assert res.status == 0
+    return res.x.reshape(e, n), -res.fun
+
+
+@pytest.mark.parametrize("seed", [0, 1, 2, 3])
+def test_capped_assignment_reaches_the_linear_programme(seed):
+    r = _rng(seed)
+    n, e, k, b, lam = 12, 4, 6, 2, 1e-3
+    S = ref.gate(r.standard_normal((n, 8)).astype(np.float32), (0.3 * r.standard_normal((8, e))).astype(np.float32))
+    A = ref.capped_assignment(S, k, b, lam, iters=20000, out_dtype=np.float64)
+    # feasible ...
+    np.testing.assert_allclose(A.sum(axis=1), k, atol=2e-3)
+    assert (A.sum(axis=0) <= b + 2e-3).all() and A.max() <= 1.0 and A.min() >= 0.0
+    # ... and optimal: the entropy term is worth at most lambda * e * n / exp(1)
+    L, best = _capped_lp(S, k, b)
+    value = float((S.T.astype(np.float64) * A).sum())
+    assert best - value <= lam * e * n / math.e + 1e-3 * float(S.max()) * e
+    # where the LP's vertex is clear-cut the near-integer A rounds to it
+    if np.abs(L - A).max() < 0.4:
+        assert (np.round(A) == np.round(L)).all()
+
+
+def test_capped_assignment_slack_cap_closed_form():
+    # column cap out of reach: per row, a_j = min(1, exp((S_j - mu)/lambda)) with mu set by sum_j a_j = k
+    r = _rng(7)
+    n, e, k, lam = 40, 3, 9, 0.05
+    S = r.random((n, e)).astype(np.float32)
+    A = ref.capped_assignment(S, k, b=float(e * k), lam=lam, iters=4000, out_dtype=np.float64)
+    for i in range(e):
+        x = S[:, i].astype(np.float64) / lam
+        lo, hi = x.min() - 50.0, x.max() + 50.0
+        for _ in range(200):                       # bisection on mu: the sum decreases with mu
+            mu = 0.5 * (lo + hi)
+            if np.minimum(1.0, np.exp(x - mu)).sum() > k:
+                lo = mu
+            else:
+                hi = mu
+        np.testing.assert_allclose(A[i], np.minimum(1.0, np.exp(x - 0.5 * (lo + hi))), atol=1e-6)
+
+
+def test_capped_assignment_special_cases():
+    # equal scores: one sweep gives the uniform matrix k/n, a fixed point when the cap allows e*k/n per column
+    S = np.full((20, 4), 0.25, np.float32)
+    A = ref.capped_assignment(S, 5, b=1.0, iters=1, out_dtype=np.float64)
+    np.testing.assert_allclose(A, 0.25, rtol=1e-12)
+    np.testing.assert_allclose(ref.capped_assignment(S, 5, b=1.0, iters=50, out_dtype=np.float64), 0.25, rtol=1e-12)
+    # a binding cap: b = 0.5 halves every column, rows are rescaled next sweep, the cap halves again:
+    # the constraints contradict each other (e*k > n*b) and A after the box step is the capped value
+    A = ref.capped_assignment(S, 5, b=0.5, iters=30, out_dtype=np.float64)
+    np.testing.assert_allclose(A.sum(axis=0), 0.5, rtol=1e-9)
+    # zero sweeps: the Gibbs kernel itself (log domain avoids the overflow of exp(S/lambda))
+    A0 = ref.capped_assignment(np.array([[0.0, 0.001]], np.float32), 1, 1, lam=1e-3, iters=0, out_dtype=np.float64)
+    np.testing.assert_allclose(A0.ravel(), [1.0, math.e], rtol=1e-6)
+    # layer: with the cap slack and the solver run to the end, the buckets are those of plain expert choice
+    w = wl.scaled(wl.WORKLOADS["cfg1"], n=32, d=8, e=4, d_ff=12, act=wl.ACT_GELU, seed=13)
+    inp = wl.make_inputs(w)
+    plain = ref.forward(inp["X"], inp["Wg"], inp["W1"], inp["W2"], w.c, w.act)
+    capped = ref.forward_capped(inp["X"], inp["Wg"], inp["W1"], inp["W2"], w.c, w.act, b=float(w.e * plain["k"]),
+                                lam=1e-3, iters=3000)
+    assert (capped["I"] == plain["I"]).all() and (capped["G"] == plain["G"]).all()
+    np.testing.assert_allclose(capped["X_out"], plain["X_out"], rtol=1e-12)
+    # and with b = 1 no token sits in more than one bucket once the solver has converged
+    capped = ref.forward_capped(inp["X"], inp["Wg"], inp["W1"], inp["W2"], 1.0, w.act, b=1.0, lam=1e-3, iters=20000)
+    assert np.bincount(capped["I"].ravel(), minlength=w.n).max() == 1
+
+
 def test_workload_generators_are_seeded_and_shaped():
     w = wl.WORKLOADS["cfg1"]
     a, b = wl.make_inputs(w), wl.make_inputs(w)
