@@ -46,6 +46,10 @@ def parse_args():
     ap.add_argument("--token-choice", type=int, default=0, metavar="M",
                     help="route with the token-choice baseline of Sec. 3.1 instead (every token's top-M experts, "
                          "buffers of floor(n*c/e) rows, dropping); reports the load imbalance as well")
+    ap.add_argument("--capped", type=float, default=0.0, metavar="B",
+                    help="expert choice with at most B experts per token (Sec. 3.3): indices from TopK(A, k), A by "
+                         "--capped-iters Dykstra sweeps at lambda = 0.001")
+    ap.add_argument("--capped-iters", type=int, default=100)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--copy-calibration", type=int, default=0, metavar="MiB",
                     help="only run a plain device-to-device copy of this many MiB five times (reference "
@@ -91,6 +95,10 @@ def main() -> int:
     if tc and (groups > 1 or w.backward or not (1 <= tc <= min(e, 8))):
         print("bench.py: --token-choice M needs a forward workload, one group and 1 <= M <= min(e, 8)", file=sys.stderr)
         return 2
+    capped = args.capped
+    if capped and (tc or groups > 1 or w.backward):
+        print("bench.py: --capped needs a forward workload, one group and no --token-choice", file=sys.stderr)
+        return 2
     k_g = m.ec_moe_capacity(n // groups, e, w.c)
     k = groups * k_g          # rows of an expert's bucket (groups = 1: Eq. 1)
     b = 2 if w.dtype == wl.DTYPE_BF16 else 4
@@ -106,6 +114,9 @@ def main() -> int:
     W2 = dev(inp["W2"]) if d_ff else None
     dt = X.dtype
     ws = m.alloc_workspace(n, d, e, k, d_ff, w.dtype)
+    if capped:   # the layer's regions, then the solver's state, then A
+        ws = torch.empty(ws.numel() + m.ec_moe_capped_workspace_bytes(n, e) + (4 * e * n + 255) // 256 * 256,
+                         dtype=torch.uint8, device="cuda")
     Xout = torch.empty((n, d), dtype=dt, device="cuda")
     K, W = args.steps, args.warmup
 
@@ -130,7 +141,9 @@ def main() -> int:
                               gr["dX"], gr["dWg"], gr["dW1"], gr["dW2"], w.act, ws)
     else:
         def step():
-            if tc:
+            if capped:
+                m.ec_moe_forward_capped(X, Wg, W1, W2, w.c, capped, 1e-3, args.capped_iters, Xout, w.act, ws)
+            elif tc:
                 m.ec_moe_forward_token_choice(X, Wg, W1, W2, w.c, tc, Xout, w.act, ws)
             elif groups == 1:
                 m.ec_moe_forward(X, Wg, W1, W2, w.c, Xout, w.act, ws)
@@ -153,8 +166,10 @@ def main() -> int:
     I = torch.empty((e, k), dtype=torch.int32, device="cuda")
     Xin = torch.empty((e, k, d), dtype=dt, device="cuda")
     Xe = torch.empty((e, k, d), dtype=dt, device="cuda") if d_ff else Xin
-    names = ["gate", "topk", "dispatch"] + (["expert_ffn"] if d_ff else []) + ["combine"]
+    names = ["gate"] + (["capped_assignment"] if capped else []) + ["topk", "dispatch"] + (["expert_ffn"] if d_ff else []) + ["combine"]
 
+    Acap = torch.empty((e, n), dtype=torch.float32, device="cuda") if capped else None
+    wscap = torch.empty(m.ec_moe_capped_workspace_bytes(n, e), dtype=torch.uint8, device="cuda") if capped else None
     Sn = torch.empty((n, e), dtype=torch.float32, device="cuda") if tc else None
     load = torch.empty((e,), dtype=torch.int32, device="cuda") if tc else None
 
@@ -162,16 +177,21 @@ def main() -> int:
         events[0].record()
         m.ec_moe_gate(X, Wg, Sn, None if tc else St, ws)
         events[1].record()
-        if tc:
+        if capped:
+            m.ec_moe_capped_assignment(St, k, capped, 1e-3, args.capped_iters, Acap, wscap)
+            events[2].record()
+            m.ec_moe_topk_tokens(Acap, k, G, I, ws)   # (weights here are entries of A; the timing is the same)
+        elif tc:
             m.ec_moe_token_choice(Sn, tc, k, G, I, load, ws)
         elif groups == 1:
             m.ec_moe_topk_tokens(St, k, G, I, ws)
         else:
             m.ec_moe_topk_tokens_grouped(St, groups, k_g, G, I, ws)
-        events[2].record()
+        j0 = 3 if capped else 2
+        events[j0].record()
         m.ec_moe_dispatch(X, I, Xin)
-        events[3].record()
-        j = 3
+        events[j0 + 1].record()
+        j = j0 + 1
         if d_ff:
             m.ec_moe_expert_ffn(Xin, W1, W2, Xe, w.act, ws)
             j += 1
@@ -193,6 +213,8 @@ def main() -> int:
                 for j, nm in enumerate(names)}
 
     alg_bytes = {
+        # per sweep: the row sums read the state once, the column/box step reads and writes both arrays
+        "capped_assignment": args.capped_iters * 5 * e * n * 8 + 2 * e * n * 4,
         "gate": n * d * b + d * e * b + n * e * 4,
         "topk": n * e * 4 + 8 * e * k,
         "dispatch": 2 * e * k * d * b + 4 * e * k,
@@ -243,7 +265,12 @@ def main() -> int:
         se = e if d_ff == 0 else max(1, min(e, int(8 * (1024 * 768 * 3072) / max(1, k * d * d_ff))))
         t0 = time.perf_counter()
         S_o = ref.gate(inp["X"], inp["Wg"])
-        if tc:
+        if capped:
+            A_o = ref.capped_assignment(S_o, k, capped, 1e-3, args.capped_iters)
+            _, I_o = ref.topk_tokens(np.ascontiguousarray(A_o.T), k)
+            G_o = np.stack([S_o[I_o[i], i] for i in range(e)])
+            Xin_o = ref.dispatch(inp["X"], I_o)
+        elif tc:
             G_o, I_o, _ = ref.token_choice(S_o, tc, k)
             Xin_o = ref.dispatch_padded(inp["X"], I_o)
         else:
@@ -275,7 +302,9 @@ def main() -> int:
         "config": {"workload": f"{w.name}: EC-MoE layer forward{' + backward' if w.backward else ''}, "
                                f"n={n} d={d} e={e} c={w.c:g} k={k} d_ff={d_ff}"
                                + (f", TopK inside {groups} groups of {n // groups} tokens" if groups > 1 else "")
-                               + (f", token-choice top-{tc} routing with dropping (baseline)" if tc else ""),
+                               + (f", token-choice top-{tc} routing with dropping (baseline)" if tc else "")
+                               + (f", at most {capped:g} experts per token (lambda=0.001, {args.capped_iters} sweeps)"
+                                  if capped else ""),
                    "act": {0: "relu", 1: "gelu", 2: "identity"}[w.act], "seed": w.seed},
         "roofline": roofline, "cpu_baseline": cpu_baseline, "stages": stages,
     }
