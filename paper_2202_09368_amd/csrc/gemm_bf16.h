@@ -41,24 +41,25 @@ enum GemmEpilogue {
                        // loads here: it names `gather_rows` 32-bit words that the launch sets to zero.
 };
 
-// GeLU with the exact-erf definition a * Phi(a); erf by the Abramowitz-Stegun rational form 7.1.26
-// (|error| < 1.5e-7), written so the negative tail has no cancellation.  Used where the result is
-// rounded to bf16 anyway.
+// GeLU with the exact-erf definition a * Phi(a); erfc by the Abramowitz-Stegun rational form 7.1.26
+// (|error| < 1.5e-7).  Used where the result is rounded to bf16 anyway, so the hardware reciprocal
+// and exp2 (1 ulp each) replace the IEEE division and the library exp.  Constants are folded:
+//   x = |a| / sqrt 2,  t = 1 / (1 + p x),  0.5 erfc(x) = t (c1 + t (c2 + ...)) exp(-x^2) with c_i halved.
 __device__ __forceinline__ float phi_tail_fast(float a, float* gauss) {  // returns 0.5*erfc(|a|/sqrt 2)
-    const float x = fabsf(a) * 0.70710678118654752440f;
-    const float t = __frcp_rn(fmaf(0.3275911f, x, 1.0f));
-    float p = fmaf(t, 1.061405429f, -1.453152027f);
-    p = fmaf(t, p, 1.421413741f);
-    p = fmaf(t, p, -0.284496736f);
-    p = fmaf(t, p, 0.254829592f);
-    const float g = __expf(-x * x);  // exp(-a^2/2)
+    const float t = __builtin_amdgcn_rcpf(fmaf(0.3275911f * 0.70710678118654752440f, fabsf(a), 1.0f));
+    float p = fmaf(t, 0.5f * 1.061405429f, 0.5f * -1.453152027f);
+    p = fmaf(t, p, 0.5f * 1.421413741f);
+    p = fmaf(t, p, 0.5f * -0.284496736f);
+    p = fmaf(t, p, 0.5f * 0.254829592f);
+    const float g = __builtin_amdgcn_exp2f((a * a) * (-0.5f * 1.44269504088896340736f));  // exp(-a^2/2)
     *gauss = g;
-    return 0.5f * p * t * g;
+    return (p * t) * g;
 }
+// a Phi(a) = max(a, 0) - |a| * (0.5 erfc(|a| / sqrt 2)): no cancellation in either tail, no select.
 __device__ __forceinline__ float gelu_erf_fast(float a) {
     float g;
     const float tail = phi_tail_fast(a, &g);
-    return a * (a >= 0.0f ? 1.0f - tail : tail);
+    return fmaf(-fabsf(a), tail, fmaxf(a, 0.0f));
 }
 // d/da of a * Phi(a) = Phi(a) + a * phi(a), phi the standard normal density.
 __device__ __forceinline__ float gelu_grad_fast(float a) {
@@ -391,7 +392,7 @@ gemm_bf16_kernel(const bf16_t* __restrict__ Aall, const bf16_t* __restrict__ Bal
         bf16_t* __restrict__ Cpre = EPI == EPI_ACT_SAVE ? reinterpret_cast<bf16_t*>(C2all) + gofs : nullptr;
         bf16_t* strip = smem + wave * 32 * EPI_STRIDE;
         constexpr int CHUNKS_PER_ROW = WN / 8;
-        constexpr int ROWS_PER_PASS = 64 / CHUNKS_PER_ROW;
+        constexpr int ROWS_PER_PASS = 64 / CHUNKS_PER_ROW;  // lanes past ROWS_PER_PASS rows idle (WN = 96)
         const int er = lane / CHUNKS_PER_ROW, ec = lane % CHUNKS_PER_ROW;
 #pragma unroll
         for (int pass = 0; pass < (EPI == EPI_ACT_SAVE ? 2 : 1); ++pass) {
@@ -418,8 +419,9 @@ gemm_bf16_kernel(const bf16_t* __restrict__ Aall, const bf16_t* __restrict__ Bal
                     const int row = rr + er;
                     const int gm = m0 + wr * WM + i * 32 + row;
                     const int gn = n0 + wc * WN + ec * 8;
-                    const uint4 v = *reinterpret_cast<const uint4*>(&strip[row * EPI_STRIDE + ec * 8]);
-                    if (gm < M && gn < N) *reinterpret_cast<uint4*>(dst + (size_t)gm * N + gn) = v;
+                    if (er < ROWS_PER_PASS && row < 32 && gm < M && gn < N)
+                        *reinterpret_cast<uint4*>(dst + (size_t)gm * N + gn) =
+                            *reinterpret_cast<const uint4*>(&strip[row * EPI_STRIDE + ec * 8]);
                 }
                 __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
                 __builtin_amdgcn_wave_barrier();
@@ -448,8 +450,9 @@ gemm_bf16_kernel(const bf16_t* __restrict__ Aall, const bf16_t* __restrict__ Bal
                     const int row = rr + er;
                     const int gm = m0 + wr * WM + i * 32 + row;
                     const int gn = n0 + wc * WN + ec * 4;
-                    const floatx4 v = *reinterpret_cast<const floatx4*>(&strip[row * EPI_STRIDE + ec * 4]);
-                    if (gm < M && gn < N) *reinterpret_cast<floatx4*>(C + (size_t)gm * N + gn) = v;
+                    if (er < ROWS_PER_PASS && row < 32 && gm < M && gn < N)
+                        *reinterpret_cast<floatx4*>(C + (size_t)gm * N + gn) =
+                            *reinterpret_cast<const floatx4*>(&strip[row * EPI_STRIDE + ec * 4]);
                 }
             } else {
                 bf16_t* __restrict__ C = reinterpret_cast<bf16_t*>(Call) + gofs;
@@ -462,7 +465,7 @@ gemm_bf16_kernel(const bf16_t* __restrict__ Aall, const bf16_t* __restrict__ Bal
                     const int row = rr + er;
                     const int gm = m0 + wr * WM + i * 32 + row;
                     const int gn = n0 + wc * WN + ec * 8;
-                    if (gm < M && gn < N) {
+                    if (er < ROWS_PER_PASS && row < 32 && gm < M && gn < N) {
                         const floatx4 v0 = *reinterpret_cast<const floatx4*>(&strip[row * EPI_STRIDE + ec * 8]);
                         const floatx4 v1 = *reinterpret_cast<const floatx4*>(&strip[row * EPI_STRIDE + ec * 8 + 4]);
                         const bf16x8 a = *reinterpret_cast<const bf16x8*>(Aux + (size_t)gm * N + gn);
