@@ -52,9 +52,12 @@ gate_mfma_kernel(const bf16_t* __restrict__ X, const bf16_t* __restrict__ Wg, fl
 #pragma unroll
         for (int r = 0; r < 16; ++r) acc[te][r] = 0.0f;
 
-    u32x4 wreg[CPT];
-    bf16x8 xreg[4];
-    auto load_chunk = [&](int kc) {
+    // Loads run PD stages ahead of their use: a wavefront has only a few MFMAs per stage, far too little to
+    // cover a trip to memory, and with one wavefront per block nothing else on the SIMD would cover it either.
+    constexpr int PD = 4;
+    u32x4 wq[PD][CPT];
+    bf16x8 xq[PD][4];
+    auto load_chunk = [&](int kc, int slot) {
 #pragma unroll
         for (int r = 0; r < CPT; ++r) {
             const int c = tid + NT * r;
@@ -62,39 +65,47 @@ gate_mfma_kernel(const bf16_t* __restrict__ X, const bf16_t* __restrict__ Wg, fl
             u32x4 v = {0u, 0u, 0u, 0u};
             if (c < CHUNKS && ech * 8 < e)  // e % 8 == 0: a chunk is all experts or all padding
                 v = *reinterpret_cast<const u32x4*>(Wg + (size_t)(kc * GATE_BK + krow) * e + ech * 8);
-            wreg[r] = v;
+            wq[slot][r] = v;
         }
 #pragma unroll
-        for (int s = 0; s < 4; ++s) xreg[s] = *reinterpret_cast<const bf16x8*>(xrow + kc * GATE_BK + s * 8);
+        for (int s = 0; s < 4; ++s) xq[slot][s] = *reinterpret_cast<const bf16x8*>(xrow + kc * GATE_BK + s * 8);
     };
 
     // The contraction index of a stage is consumed in the order (half, step): lanes 0-31 own elements
     // [0,32) of the stage, lanes 32-63 own [32,64), so a lane's X values are 64 contiguous bytes.
     const int w_frag = (half * 32 + (l16 >> 2)) * PITCH + ((lane >> 4) & 1) * 16 + (l16 & 3) * 4;
     const int nk = d / GATE_BK;
-    load_chunk(0);
-    for (int kc = 0; kc < nk; ++kc) {
-        __syncthreads();
 #pragma unroll
-        for (int r = 0; r < CPT; ++r) {
-            const int c = tid + NT * r;
-            const int krow = c / (E_PAD / 8), ech = c % (E_PAD / 8);
-            if (c < CHUNKS) *reinterpret_cast<u32x4*>(&Wk[krow * PITCH + ech * 8]) = wreg[r];
-        }
-        __syncthreads();
-        bf16x8 xcur[4];
+    for (int u = 0; u < PD; ++u)
+        if (u < nk) load_chunk(u, u);
+    for (int kc0 = 0; kc0 < nk; kc0 += PD) {
 #pragma unroll
-        for (int s = 0; s < 4; ++s) xcur[s] = xreg[s];
-        if (kc + 1 < nk) load_chunk(kc + 1);
+        for (int u = 0; u < PD; ++u) {
+            const int kc = kc0 + u;
+            if (kc < nk) {  // uniform
+                __syncthreads();
 #pragma unroll
-        for (int s = 0; s < 4; ++s) {
+                for (int r = 0; r < CPT; ++r) {
+                    const int c = tid + NT * r;
+                    const int krow = c / (E_PAD / 8), ech = c % (E_PAD / 8);
+                    if (c < CHUNKS) *reinterpret_cast<u32x4*>(&Wk[krow * PITCH + ech * 8]) = wq[u][r];
+                }
+                __syncthreads();
+                bf16x8 xcur[4];
 #pragma unroll
-            for (int te = 0; te < ET; ++te) {
-                const bf16_t* p0 = &Wk[w_frag + s * 8 * PITCH + te * 32];
-                bf16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4bf16((lds_bf16x4*)(p0));
-                bf16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4bf16((lds_bf16x4*)(p0 + 4 * PITCH));
-                bf16x8 a = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
-                acc[te] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, xcur[s], acc[te], 0, 0, 0);
+                for (int s = 0; s < 4; ++s) xcur[s] = xq[u][s];
+                if (kc + PD < nk) load_chunk(kc + PD, u);
+#pragma unroll
+                for (int s = 0; s < 4; ++s) {
+#pragma unroll
+                    for (int te = 0; te < ET; ++te) {
+                        const bf16_t* p0 = &Wk[w_frag + s * 8 * PITCH + te * 32];
+                        bf16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4bf16((lds_bf16x4*)(p0));
+                        bf16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4bf16((lds_bf16x4*)(p0 + 4 * PITCH));
+                        bf16x8 a = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
+                        acc[te] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, xcur[s], acc[te], 0, 0, 0);
+                    }
+                }
             }
         }
     }
