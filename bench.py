@@ -30,8 +30,8 @@ PEAK_BF16_TFLOPS = 2500.0      # MI355X dense bf16 MFMA, published
 
 # HBM bytes per expert-GEMM launch (mean of the two launches of one FFN call) from the rocprofv3
 # --pmc FETCH_SIZE / WRITE_SIZE runs summarised in profiles/cfg2_forward_hbm_traffic.txt
-# (first product 125.48 MiB read + 96.00 MiB written, second 172.61 + 24.38); None where not measured.
-MEASURED_FFN_TRAFFIC_BYTES = {"cfg2": int((125.48 + 96.00 + 172.61 + 24.38) * 1048576 / 2)}
+# (first product 114.47 MiB read + 96.00 MiB written, second 172.19 + 24.00); None where not measured.
+MEASURED_FFN_TRAFFIC_BYTES = {"cfg2": int((114.47 + 96.00 + 172.19 + 24.00) * 1048576 / 2)}
 
 
 def parse_args():
