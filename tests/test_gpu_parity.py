@@ -167,6 +167,10 @@ def test_cfg1_fp32_full(m, ref):
     ("cfg3", dict(n=4096, d=128, e=64, d_ff=256)),
     ("cfg5", dict(n=8192, d=512, e=256)),                        # skewed routing-only, e=256
     ("cfg5", dict(n=3000, d=264, e=40, c=1.0)),                  # d not a multiple of 64: generic gate
+    ("cfg5", dict(n=4096, d=64, e=1024, c=1.0)),                 # the largest expert count the ABI accepts (k = 4)
+    ("cfg1", dict(n=128, d=32, e=4, c=4.0, d_ff=64)),            # k = n: every expert takes every token
+    ("cfg1", dict(n=1, d=4, e=1, c=1.0, d_ff=4)),                # one token, one expert
+    ("cfg2", dict(n=16, d=64, e=16, c=1.0, d_ff=64)),            # k = 1, buckets of a single row
 ])
 def test_reduced_shapes(m, ref, name, kw):
     w = wl.scaled(wl.WORKLOADS[name], **kw)
