@@ -203,7 +203,10 @@ int ec_moe_forward_capped(const void* X, const void* Wg, const void* W1, const v
  * trained through the top-k function).  Inputs: dY [n,d] and the forward's
  * X, Wg, W1, W2, S [n,e], G, I [e,k], X_in [e,k,d], A, H [e,k,d_ff], X_e [e,k,d].
  * Outputs: dX [n,d] in `dtype`; dWg [d,e], dW1 [e,d,d_ff], dW2 [e,d_ff,d] float.
- * ws must come from ec_moe_workspace_bytes(..., with_backward = 1). */
+ * ws must come from ec_moe_workspace_bytes(..., with_backward = 1).
+ * The pass depends on the routing only through S, G, I and the saved bucket tensors, so it also
+ * serves ec_moe_forward_grouped (k = groups * k_g).  Every I[i,j] must lie in [0,n): the buffers
+ * of token-choice routing, which may hold -1, are not supported here. */
 int ec_moe_backward(const void* dY, const void* X, const void* Wg, const void* W1, const void* W2,
                     const float* S, const float* G, const int32_t* I,
                     const void* Xin, const void* A, const void* H, const void* Xe,

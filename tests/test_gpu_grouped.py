@@ -115,3 +115,42 @@ def test_grouped_forward(m, ref, base, kw, groups):
         m.ec_moe_forward_grouped(t["X"], t["Wg"], t.get("W1"), t.get("W2"), w.c, 1, Xout2, w.act, ws1)
         torch.cuda.synchronize()
         assert (to_host(Xout1) == to_host(Xout2)).all()
+
+
+@pytest.mark.parametrize("base,kw,groups,tol", [
+    ("cfg1", dict(n=256, d=64, e=8, c=2.0, d_ff=128, act=wl.ACT_GELU), 4, 2e-4),
+    ("cfg2", dict(n=2048, d=256, e=16, d_ff=512), 8, 2e-2),
+])
+def test_grouped_backward(m, ref, base, kw, groups, tol):
+    # the backward pass only sees the buckets (S, G, I and the saved activations), so it serves the
+    # grouped routing unchanged: k is the bucket length groups * k_g
+    w = wl.scaled(wl.WORKLOADS[base], backward=True, **kw)
+    inp = wl.make_inputs(w)
+    n, d, e, f = w.n, w.d, w.e, w.d_ff
+    k = groups * ref.capacity(n // groups, w.c, e)
+    _p(f"[grouped backward] {base} n={n} e={e} groups={groups} k={k}")
+    dt = torch_dtype(w)
+    t = {key: to_dev(inp[key]) for key in ("X", "Wg", "W1", "W2", "dY")}
+    ws = m.alloc_workspace(n, d, e, k, f, w.dtype, with_backward=True)
+    dev = dict(device="cuda")
+    S = torch.empty((n, e), dtype=torch.float32, **dev)
+    G = torch.empty((e, k), dtype=torch.float32, **dev)
+    I = torch.empty((e, k), dtype=torch.int32, **dev)
+    Xin = torch.empty((e, k, d), dtype=dt, **dev)
+    A = torch.empty((e, k, f), dtype=dt, **dev)
+    H = torch.empty((e, k, f), dtype=dt, **dev)
+    Xe = torch.empty((e, k, d), dtype=dt, **dev)
+    Xout = torch.empty((n, d), dtype=dt, **dev)
+    m.ec_moe_forward_grouped(t["X"], t["Wg"], t["W1"], t["W2"], w.c, groups, Xout, w.act, ws, S_out=S, G_out=G,
+                             I_out=I, Xin_out=Xin, A_out=A, H_out=H, Xe_out=Xe)
+    dX = torch.empty((n, d), dtype=dt, **dev)
+    dWg = torch.empty((d, e), dtype=torch.float32, **dev)
+    dW1 = torch.empty((e, d, f), dtype=torch.float32, **dev)
+    dW2 = torch.empty((e, f, d), dtype=torch.float32, **dev)
+    m.ec_moe_backward(t["dY"], t["X"], t["Wg"], t["W1"], t["W2"], S, G, I, Xin, A, H, Xe, dX, dWg, dW1, dW2, w.act, ws)
+    torch.cuda.synchronize()
+    g = ref.backward(inp["X"], inp["Wg"], inp["W1"], inp["W2"], w.act, to_host(S), to_host(G), to_host(I), inp["dY"])
+    for key, got in (("dX", dX), ("dWg", dWg), ("dW1", dW1), ("dW2", dW2)):
+        err = max_rel_err(to_host(got), g[key])
+        _p(f"[grouped backward] {key} max rel err {err:.3e}")
+        assert err <= (1.5 * tol if key == "dX" else tol)
