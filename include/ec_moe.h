@@ -129,7 +129,9 @@ int ec_moe_combine(const void* Xe, const float* G, const int32_t* I, void* Xout,
 /* Sec. 3.2, Eq. 1-4 in one call on one stream: gate, TopK over tokens,
  * dispatch, expert FFN, combine.  k = floor(n*c/e) as in ec_moe_capacity.
  * W1 = W2 = NULL with act = EC_ACT_IDENTITY runs identity experts (routing
- * only: X_e = X_in); d_ff is then ignored.
+ * only: X_e = X_in); d_ff is then ignored.  The gather of Eq. 3 is fused where nobody asks for its
+ * result: into the first expert product's tile loads, or, with identity experts, into the combine's
+ * row reads (X_in is then never written; pass Xin_out or Xe_out to have it materialised).
  * Optional outputs, each NULL to skip: S_out [n,e], G_out [e,k], I_out [e,k]
  * (int32), Xin_out [e,k,d], A_out / H_out [e,k,d_ff], Xe_out [e,k,d] -- the
  * tensors ec_moe_backward consumes.  X_out [n,d] is required. */

@@ -201,20 +201,29 @@ static int forward_impl(const void* X, const void* Wg, const void* W1, const voi
                      ix.use_slots ? ix.slot_cnt : nullptr, ix.slots, ix.slot_cap, ix.use_slots ? nullptr : ix.bitmap, st,
                      groups);
     if (rc != EC_OK) return rc;
-    // The bucket gather is fused into the first expert product unless the caller wants X_in itself.
+    // The bucket gather is fused into the first expert product unless the caller wants X_in itself.  With
+    // identity experts X_e = X_in = the gathered rows of X: unless the caller asks for one of them, the
+    // combine reads those rows in place through I.
     const bool fused_gather = !identity && Xin_out == nullptr && ffn_can_gather(dtype, n, k, d, d_ff);
+    if (identity) {
+        void* rows = Xin_out ? Xin_out : Xe_out;
+        if (rows == nullptr) return launch_combine(X, G, I, Xout, n, d, e, k, dtype, ix, st, nullptr, false, I);
+        rc = launch_dispatch(X, I, rows, n, d, e, k, dtype, st);
+        if (rc != EC_OK) return rc;
+        if (Xin_out && Xe_out) {
+            rc = launch_dispatch(X, I, Xe_out, n, d, e, k, dtype, st);
+            if (rc != EC_OK) return rc;
+        }
+        return launch_combine(rows, G, I, Xout, n, d, e, k, dtype, ix, st);
+    }
     if (!fused_gather) {
         rc = launch_dispatch(X, I, Xin, n, d, e, k, dtype, st);
         if (rc != EC_OK) return rc;
     }
-    const void* Xe = Xin;  // identity experts
-    if (!identity) {
-        void* H = H_out ? H_out : at(ws, L.h);
-        void* Xe_w = Xe_out ? Xe_out : at(ws, L.xe);
-        rc = launch_ffn(fused_gather ? nullptr : Xin, X, I, n, W1, W2, Xe_w, A_out, H, e, k, d, d_ff, act, dtype, st);
-        if (rc != EC_OK) return rc;
-        Xe = Xe_w;
-    }
+    void* H = H_out ? H_out : at(ws, L.h);
+    void* Xe = Xe_out ? Xe_out : at(ws, L.xe);
+    rc = launch_ffn(fused_gather ? nullptr : Xin, X, I, n, W1, W2, Xe, A_out, H, e, k, d, d_ff, act, dtype, st);
+    if (rc != EC_OK) return rc;
     return launch_combine(Xe, G, I, Xout, n, d, e, k, dtype, ix, st);
 }
 

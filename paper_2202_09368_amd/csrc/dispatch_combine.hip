@@ -188,7 +188,7 @@ template <typename T, int VEC, int CAP>
 __global__ void __launch_bounds__(256)
 combine_kernel(const T* __restrict__ Xe, const float* __restrict__ G, const int32_t* __restrict__ offsets,
                const int32_t* __restrict__ inv, T* __restrict__ Xout, int n, int d, int tpr,
-               const float* __restrict__ addend) {
+               const float* __restrict__ addend, const int32_t* __restrict__ src_rows) {
     typedef T vec_t __attribute__((ext_vector_type(VEC)));
     constexpr int NRAW = CAP > 0 ? CAP : 1;
     const int tok_per_block = 256 / tpr;
@@ -223,7 +223,10 @@ combine_kernel(const T* __restrict__ Xe, const float* __restrict__ G, const int3
                     r = inv[beg + p];
                 }
                 const float g = G != nullptr ? G[r] : 1.0f;  // no weights: plain scatter-add of rows
-                vec_t x = *reinterpret_cast<const vec_t*>(Xe + (size_t)r * d + (size_t)v * VEC);
+                // src_rows: bucket row r is row src_rows[r] of Xe (identity experts: X_e[i,j,:] = X[I[i,j],:], the
+                // gather of Eq. 3 read in place instead of through a materialised X_in)
+                const size_t src = src_rows != nullptr ? (size_t)src_rows[r] : (size_t)r;
+                vec_t x = *reinterpret_cast<const vec_t*>(Xe + src * d + (size_t)v * VEC);
 #pragma unroll
                 for (int q = 0; q < VEC; ++q) acc[q] = fmaf(g, Cvt<T>::to_f32(x[q]), acc[q]);
             }
@@ -278,10 +281,11 @@ int launch_combine_csr(const int32_t* I, int64_t n, int64_t e, int64_t k, const 
 }
 
 // Applies Eq. 4 given a filled index (slot lists, or the bitmap from which the CSR lists are finished here).
-// G == nullptr adds the rows unweighted; `addend` (fp32 [n,d], optional) is the starting value of every row.
+// G == nullptr adds the rows unweighted; `addend` (fp32 [n,d], optional) is the starting value of every row;
+// `src_rows` (optional, [e*k]) redirects bucket row r to row src_rows[r] of Xe.
 int launch_combine(const void* Xe, const float* G, const int32_t* I, void* Xout, int64_t n, int64_t d,
                    int64_t e, int64_t k, int dtype, const CombineIndex& ix, hipStream_t stream,
-                   const float* addend, bool csr_ready) {
+                   const float* addend, bool csr_ready, const int32_t* src_rows) {
     const int32_t* offs = ix.slot_cnt;
     const int32_t* list = ix.slots;
     if (!ix.use_slots) {
@@ -300,16 +304,16 @@ int launch_combine(const void* Xe, const float* G, const int32_t* I, void* Xout,
         dim3 grid((unsigned)blocks), block(256);                                                              \
         if (!ix.use_slots)                                                                                    \
             hipLaunchKernelGGL((combine_kernel<TYPE, VECV, 0>), grid, block, 0, stream, (const TYPE*)Xe, G,   \
-                               offs, list, (TYPE*)Xout, (int)n, (int)d, tpr, addend);                                 \
+                               offs, list, (TYPE*)Xout, (int)n, (int)d, tpr, addend, src_rows);                                 \
         else if (ix.slot_cap == 4)                                                                            \
             hipLaunchKernelGGL((combine_kernel<TYPE, VECV, 4>), grid, block, 0, stream, (const TYPE*)Xe, G,   \
-                               offs, list, (TYPE*)Xout, (int)n, (int)d, tpr, addend);                                 \
+                               offs, list, (TYPE*)Xout, (int)n, (int)d, tpr, addend, src_rows);                                 \
         else if (ix.slot_cap == 8)                                                                            \
             hipLaunchKernelGGL((combine_kernel<TYPE, VECV, 8>), grid, block, 0, stream, (const TYPE*)Xe, G,   \
-                               offs, list, (TYPE*)Xout, (int)n, (int)d, tpr, addend);                                 \
+                               offs, list, (TYPE*)Xout, (int)n, (int)d, tpr, addend, src_rows);                                 \
         else                                                                                                  \
             hipLaunchKernelGGL((combine_kernel<TYPE, VECV, 16>), grid, block, 0, stream, (const TYPE*)Xe, G,  \
-                               offs, list, (TYPE*)Xout, (int)n, (int)d, tpr, addend);                                 \
+                               offs, list, (TYPE*)Xout, (int)n, (int)d, tpr, addend, src_rows);                                 \
     } while (0)
     if (dtype == EC_BF16) EC_COMBINE_LAUNCH(bf16_t, 8, d / 8);
     else if (d % 4 == 0) EC_COMBINE_LAUNCH(float, 4, d / 4);

@@ -271,6 +271,29 @@ def test_topk_cases(m, ref, n, e, k, kind):
     _topk_case(m, ref, St, k)
 
 
+def test_identity_forward_optional_outputs(m, ref):
+    # identity experts: the gather is read in place by the combine unless X_in or X_e is asked for
+    w = wl.scaled(wl.WORKLOADS["cfg5"], n=2048, d=128, e=32)
+    inp = wl.make_inputs(w)
+    k = w.k
+    ws = m.alloc_workspace(w.n, w.d, w.e, k, 0, w.dtype)
+    X, Wg = to_dev(inp["X"]), to_dev(inp["Wg"])
+    outs = []
+    for want_in, want_e in ((False, False), (True, False), (False, True), (True, True)):
+        Xout = torch.full((w.n, w.d), float("nan"), dtype=torch.bfloat16, device="cuda")
+        I = torch.empty((w.e, k), dtype=torch.int32, device="cuda")
+        Xin = torch.full((w.e, k, w.d), float("nan"), dtype=torch.bfloat16, device="cuda") if want_in else None
+        Xe = torch.full((w.e, k, w.d), float("nan"), dtype=torch.bfloat16, device="cuda") if want_e else None
+        m.ec_moe_forward(X, Wg, None, None, w.c, Xout, w.act, ws, I_out=I, Xin_out=Xin, Xe_out=Xe)
+        torch.cuda.synchronize()
+        gathered = ref.dispatch(inp["X"], to_host(I))
+        for t in (Xin, Xe):
+            if t is not None:
+                assert (to_host(t) == gathered).all()
+        outs.append(to_host(Xout))
+    assert all((o == outs[0]).all() for o in outs[1:])
+
+
 # ------------------------------------------------------------- determinism ---
 def test_forward_is_deterministic(m):
     w = wl.scaled(wl.WORKLOADS["cfg2"], n=2048, d=256, e=16, d_ff=512)
