@@ -293,6 +293,7 @@ struct TopkRegShared {
     unsigned int wave_cnt[TOPK_WAVES];
     unsigned int cand_key[TOPK_CAND_MAX];  // candidates for the cut-off: key and ~token, kept as separate
     unsigned int cand_ntok[TOPK_CAND_MAX]; // 32-bit words (64-bit keys would double the register need)
+    unsigned int above_cnt[TOPK_CAND_MAX]; // candidates ranked above each candidate
     unsigned int cut_key, cut_ntok;
     unsigned int slot;
 };
@@ -336,6 +337,7 @@ topk_tokens_reg_kernel(const float* __restrict__ St, int n_total, int n, int k, 
     (&sh.hist[0][0][0])[tid] = 0u;         // buffers 0 and 1 start clean (1024 words each)
     (&sh.hist[1][0][0])[tid] = 0u;
     if (tid == 0) sh.slot = 0u;
+    if (tid < TOPK_CAND_MAX) sh.above_cnt[tid] = 0u;
     __syncthreads();
 #pragma unroll
     for (int w = 0; w < TOPK_WAVES; ++w) {
@@ -420,14 +422,23 @@ topk_tokens_reg_kernel(const float* __restrict__ St, int n_total, int n, int k, 
             }
         }
         __syncthreads();
-        if (tid < (int)cand) {
-            const unsigned int mhi = sh.cand_key[tid], mlo = sh.cand_ntok[tid];
+        // the candidate with exactly remaining-1 candidates above it is the cut-off; four threads share
+        // the count of one candidate
+        static_assert(TOPK_THREADS == 4 * TOPK_CAND_MAX, "four threads per candidate");
+        const unsigned int c = (unsigned int)tid & (TOPK_CAND_MAX - 1), part = (unsigned int)tid / TOPK_CAND_MAX;
+        if (c < cand) {
+            const unsigned int mhi = sh.cand_key[c], mlo = sh.cand_ntok[c];
             unsigned int above = 0;
-            for (unsigned int j = 0; j < cand; ++j) {
+            for (unsigned int j = part; j < cand; j += 4) {
                 const unsigned int ohi = sh.cand_key[j], olo = sh.cand_ntok[j];
                 above += (ohi > mhi) | ((ohi == mhi) & (olo > mlo));
             }
-            if (above == remaining - 1u) { sh.cut_key = mhi; sh.cut_ntok = mlo; }
+            if (above != 0u) atomicAdd(&sh.above_cnt[c], above);
+        }
+        __syncthreads();
+        if (tid < (int)cand && sh.above_cnt[tid] == remaining - 1u) {
+            sh.cut_key = sh.cand_key[tid];
+            sh.cut_ntok = sh.cand_ntok[tid];
         }
     } else {
         // Exact ties at the threshold score: the cut-off is the `remaining`-th tied token in token order.
