@@ -309,6 +309,38 @@ def test_forward_is_deterministic(m):
     assert (outs[0] == outs[1]).all() and (outs[0] == outs[2]).all()
 
 
+def test_forward_under_graph_capture(m):
+    # the forward allocates nothing and clears its counters with kernels, so a caller may capture it;
+    # every replay, with eager work and synchronisations in between, must equal the eager result
+    w = wl.scaled(wl.WORKLOADS["cfg3"], n=4096, d=256, e=64, d_ff=512)
+    inp = wl.make_inputs(w)
+    ws = m.alloc_workspace(w.n, w.d, w.e, w.k, w.d_ff, w.dtype)
+    t = {key: to_dev(inp[key]) for key in ("X", "Wg", "W1", "W2")}
+    Xout = torch.empty((w.n, w.d), dtype=torch.bfloat16, device="cuda")
+
+    def step():
+        m.ec_moe_forward(t["X"], t["Wg"], t["W1"], t["W2"], w.c, Xout, w.act, ws)
+
+    step()
+    torch.cuda.synchronize()
+    eager = to_host(Xout)
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        step()
+    torch.cuda.current_stream().wait_stream(side)
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        step()
+    torch.cuda.synchronize()
+    for _ in range(4):
+        Xout.fill_(1.0)                      # eager work between the replays
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        assert (to_host(Xout) == eager).all()
+
+
 def test_zero_gate_all_ties(m, ref):
     # Wg = 0: S = 1/e everywhere, every expert takes tokens 0..k-1 in order
     w = wl.scaled(wl.WORKLOADS["cfg1"], n=512, d=32, e=4, d_ff=64)
