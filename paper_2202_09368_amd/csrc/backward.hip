@@ -69,7 +69,11 @@ bwd_dz_kernel(const float* __restrict__ S, const float* __restrict__ dG, const i
             for (int i = lane; i < e; i += kWave) {
                 const float z = S[(size_t)l * e + i] * (ds[wave][i] - dot);
                 dZ[(size_t)l * e + i] = z;
-                if (dZb != nullptr) dZb[(size_t)l * e + i] = static_cast<bf16_t>(z);
+                if (dZb != nullptr) {  // z = hi + lo with both in bf16 (error 2^-17 |z|), row layout [hi(e) | lo(e)]
+                    const bf16_t hi = static_cast<bf16_t>(z);
+                    dZb[(size_t)l * 2 * e + i] = hi;
+                    dZb[(size_t)l * 2 * e + e + i] = static_cast<bf16_t>(z - static_cast<float>(hi));
+                }
             }
         }
         __syncthreads();
@@ -180,11 +184,39 @@ reduce_splits_kernel(const float* __restrict__ part, float* __restrict__ out, lo
     }
 }
 
+// Partials laid out [splits][d][2e] (products with the high and the low half of dZ side by side):
+// out[t][i] = sum over splits, in split order, of (part[s][t][i] + part[s][t][e + i]).
+__global__ void __launch_bounds__(256)
+reduce_splits_halves_kernel(const float* __restrict__ part, float* __restrict__ out, int d, int e, int splits) {
+    const long long count = (long long)d * e;
+    for (long long q = (long long)blockIdx.x * 256 + threadIdx.x; q < count; q += (long long)gridDim.x * 256) {
+        const long long t = q / e, i = q % e;
+        float s = 0.0f;
+        for (int p = 0; p < splits; ++p) {
+            const float* row = part + ((size_t)p * d + t) * 2 * e;
+            s += row[i] + row[e + i];
+        }
+        out[q] = s;
+    }
+}
+
+// Wg2[t][:] = [Wg[t][:] | Wg[t][:]]: the other operand of the product with [hi | lo].
+__global__ void __launch_bounds__(256)
+duplicate_columns_kernel(const bf16_t* __restrict__ Wg, bf16_t* __restrict__ Wg2, int d, int e) {
+    const long long count = (long long)d * e;
+    for (long long q = (long long)blockIdx.x * 256 + threadIdx.x; q < count; q += (long long)gridDim.x * 256) {
+        const long long t = q / e, i = q % e;
+        const bf16_t v = Wg[q];
+        Wg2[t * 2 * e + i] = v;
+        Wg2[t * 2 * e + e + i] = v;
+    }
+}
+
 // ---------------------------------------------------------------------------
 // Workspace of the backward pass (after the forward layout, at L.bwd).
 // ---------------------------------------------------------------------------
 struct BwdLayout {
-    size_t dxe, dg, da, dxin, dz, dzb, dxz, wg_part, total;
+    size_t dxe, dg, da, dxin, dz, dzb, dxz, wg_part, wg2, total;
     int splits;
     int64_t split_len;
 };
@@ -199,11 +231,12 @@ static BwdLayout bwd_layout(int64_t n, int64_t d, int64_t e, int64_t k, int64_t 
     B.dxe = take((size_t)e * k * d * es);
     B.dg = take((size_t)e * k * 4);
     B.da = take((size_t)e * k * d_ff * es);
-    B.dxin = take((size_t)e * k * d * es);
+    B.dxin = take((size_t)e * k * d * 4);  // fp32 on the matrix-core path (kept unrounded), else `es` bytes per element
     B.dz = take((size_t)n * e * 4);
-    B.dzb = take((size_t)n * e * 2);
+    B.dzb = take((size_t)n * e * 2 * 2);                   // [n][hi | lo]
     B.dxz = take((size_t)n * d * 4);
-    B.wg_part = take((size_t)B.splits * d * e * 4);
+    B.wg_part = take((size_t)B.splits * d * e * 2 * 4);    // [splits][d][2e] on the matrix-core path
+    B.wg2 = take((size_t)d * e * 2 * 2);
     B.total = off;
     return B;
 }
@@ -234,6 +267,14 @@ static int backward_typed(const T* dY, const T* X, const T* Wg, const T* W1, con
     const bool mfma = BF && gemm_bf16_shape_ok(k, d_ff, d) && gemm_bf16_shape_ok(k, d, d_ff) &&
                       gemm_bf16_shape_ok(d_ff, d, k, false, true) && gemm_bf16_shape_ok(d, d_ff, k, false, true);
 
+    // Matrix-core path for the two gate products (dWg = X^T dZ, dZ Wg^T): whole splits of 512 tokens, experts
+    // a multiple of 32 (the contraction of the second product is 2e), 16-byte rows.  dZ enters as hi + lo,
+    // two bf16 numbers per value, so the products see it to 2^-17: dZ is a gradient of the fp32 scores and a
+    // single bf16 rounding would cost a third of the error budget of dWg.
+    const bool mfma_gate = BF && (n % B.split_len) == 0 && (e % 32) == 0 && (d % 8) == 0 &&
+                           gemm_bf16_shape_ok(d, 2 * e, B.split_len, false, true) && gemm_bf16_shape_ok(n, d, 2 * e);
+    bf16_t* Wg2 = reinterpret_cast<bf16_t*>(base + B.wg2);
+
     // Eq. 4 backwards: dX_e, dG
     {
         long long blocks = ceil_div(rows, 4);
@@ -258,8 +299,8 @@ static int backward_typed(const T* dY, const T* X, const T* Wg, const T* W1, con
             // dW1[i] = X_in[i]^T dA[i]    -> fp32 [d][d_ff]
             gemm_bf16_launch<256, 256, 2, 1, true, false, EPI_F32, EC_ACT_IDENTITY>(bXin, (const bf16_t*)dA, dW1, nullptr, Gn,
                                                                                     D, F, Mk, nullptr, 0, stream);
-            // dX_in[i] = dA[i] W1[i]^T    (B = W1 stored [d][d_ff] = [N][K])
-            gemm_bf16_launch<256, 256, 2, 1, false, true, EPI_ACT, EC_ACT_IDENTITY>((const bf16_t*)dA, (const bf16_t*)W1, dXin,
+            // dX_in[i] = dA[i] W1[i]^T    (B = W1 stored [d][d_ff] = [N][K]); kept in fp32: it is only summed into dX
+            gemm_bf16_launch<256, 256, 2, 1, false, true, EPI_F32, EC_ACT_IDENTITY>((const bf16_t*)dA, (const bf16_t*)W1, dXin,
                                                                                     nullptr, Gn, Mk, D, F, nullptr, 0, stream);
         }
     } else {
@@ -287,8 +328,24 @@ static int backward_typed(const T* dY, const T* X, const T* Wg, const T* W1, con
         long long blocks = ceil_div(n, 4);
         if (blocks > 65536) blocks = 65536;
         hipLaunchKernelGGL(bwd_dz_kernel, dim3((unsigned)blocks), dim3(256), 0, stream, S, dG, ix.offsets, ix.inv, dZ,
-                           (bf16_t*)nullptr, (int)n, (int)e, (int)k);
+                           mfma_gate ? dZb : (bf16_t*)nullptr, (int)n, (int)e, (int)k);
     }
+    if (mfma_gate) {
+        if constexpr (BF) {
+            // partial[s] = X[s*512 ..]^T [hi | lo][s*512 ..]: one group per split, both operands row-indexed
+            // by the token; the fixed-order sum over the splits folds the two halves
+            gemm_bf16_launch<256, 128, 2, 1, true, false, EPI_F32, EC_ACT_IDENTITY>(
+                (const bf16_t*)X, dZb, wg_part, nullptr, B.splits, D, 2 * (int)e, (int)B.split_len, nullptr, 0, stream);
+            const long long cnt = (long long)d * e, blocks = (cnt + 255) / 256;
+            const unsigned gridr = (unsigned)(blocks > 4096 ? 4096 : blocks);
+            hipLaunchKernelGGL(reduce_splits_halves_kernel, dim3(gridr), dim3(256), 0, stream, wg_part, dWg, D, (int)e,
+                               B.splits);
+            // dXz = [hi | lo] [Wg | Wg]^T: contraction over 2e, the second operand stored [d][2e] = [N][K]
+            hipLaunchKernelGGL(duplicate_columns_kernel, dim3(gridr), dim3(256), 0, stream, (const bf16_t*)Wg, Wg2, D, (int)e);
+            gemm_bf16_launch<256, 256, 2, 1, false, true, EPI_F32, EC_ACT_IDENTITY>(dZb, Wg2, dXz, nullptr, 1, (int)n, D,
+                                                                                    2 * (int)e, nullptr, 0, stream);
+        }
+    } else {
     {   // partial[s] = X[s*len .. ]^T dZ[s*len .. ]   (the last split is shorter; its K is passed per launch)
         const int full = (int)(n / B.split_len);
         if (full > 0)
@@ -306,11 +363,11 @@ static int backward_typed(const T* dY, const T* X, const T* Wg, const T* W1, con
     }
     // dXz = dZ Wg^T  (Wg stored [d][e] = [N][K])
     gemm_plain<float, T, float, false, true>(dZ, Wg, dXz, 1, (int)n, D, (int)e, 0, 0, 0, stream);
+    }
     rc = check_launch();
     if (rc != EC_OK) return rc;
     // dX = dXz + scatter-add of dX_in rows, expert-ascending, rounded once
-    (void)dZb;
-    return launch_combine(dXin, nullptr, I, dX, n, d, e, k, dtype, ix, stream, dXz, true);
+    return launch_combine(dXin, nullptr, I, dX, n, d, e, k, dtype, ix, stream, dXz, true, nullptr, BF && mfma);
 }
 
 int launch_backward(const void* dY, const void* X, const void* Wg, const void* W1, const void* W2, const float* S,

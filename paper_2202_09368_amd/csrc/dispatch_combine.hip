@@ -184,12 +184,13 @@ inverse_index_kernel(const int32_t* __restrict__ I, const uint32_t* __restrict__
 // step and accumulates in fp32.  CAP = 0: rows come from the CSR lists (expert-ascending).
 // CAP > 0: rows come from the token's slot list (capacity CAP), visited in ascending row order
 // by repeated minimum -- the lists are short, the capacity factor on average.
-template <typename T, int VEC, int CAP>
+template <typename T, int VEC, int CAP, typename TRow = T>
 __global__ void __launch_bounds__(256)
-combine_kernel(const T* __restrict__ Xe, const float* __restrict__ G, const int32_t* __restrict__ offsets,
+combine_kernel(const TRow* __restrict__ Xe, const float* __restrict__ G, const int32_t* __restrict__ offsets,
                const int32_t* __restrict__ inv, T* __restrict__ Xout, int n, int d, int tpr,
                const float* __restrict__ addend, const int32_t* __restrict__ src_rows) {
     typedef T vec_t __attribute__((ext_vector_type(VEC)));
+    typedef TRow row_vec_t __attribute__((ext_vector_type(VEC)));  // bucket rows may be fp32 where the output is bf16
     constexpr int NRAW = CAP > 0 ? CAP : 1;
     const int tok_per_block = 256 / tpr;
     const int sub = threadIdx.x / tpr, t = threadIdx.x % tpr;
@@ -226,9 +227,9 @@ combine_kernel(const T* __restrict__ Xe, const float* __restrict__ G, const int3
                 // src_rows: bucket row r is row src_rows[r] of Xe (identity experts: X_e[i,j,:] = X[I[i,j],:], the
                 // gather of Eq. 3 read in place instead of through a materialised X_in)
                 const size_t src = src_rows != nullptr ? (size_t)src_rows[r] : (size_t)r;
-                vec_t x = *reinterpret_cast<const vec_t*>(Xe + src * d + (size_t)v * VEC);
+                row_vec_t x = *reinterpret_cast<const row_vec_t*>(Xe + src * d + (size_t)v * VEC);
 #pragma unroll
-                for (int q = 0; q < VEC; ++q) acc[q] = fmaf(g, Cvt<T>::to_f32(x[q]), acc[q]);
+                for (int q = 0; q < VEC; ++q) acc[q] = fmaf(g, Cvt<TRow>::to_f32(x[q]), acc[q]);
             }
             vec_t o;
 #pragma unroll
@@ -282,10 +283,11 @@ int launch_combine_csr(const int32_t* I, int64_t n, int64_t e, int64_t k, const 
 
 // Applies Eq. 4 given a filled index (slot lists, or the bitmap from which the CSR lists are finished here).
 // G == nullptr adds the rows unweighted; `addend` (fp32 [n,d], optional) is the starting value of every row;
-// `src_rows` (optional, [e*k]) redirects bucket row r to row src_rows[r] of Xe.
+// `src_rows` (optional, [e*k]) redirects bucket row r to row src_rows[r] of Xe; `rows_f32`: the bucket rows are
+// fp32 although the output is bf16 (the last product of the backward pass is kept unrounded).
 int launch_combine(const void* Xe, const float* G, const int32_t* I, void* Xout, int64_t n, int64_t d,
                    int64_t e, int64_t k, int dtype, const CombineIndex& ix, hipStream_t stream,
-                   const float* addend, bool csr_ready, const int32_t* src_rows) {
+                   const float* addend, bool csr_ready, const int32_t* src_rows, bool rows_f32) {
     const int32_t* offs = ix.slot_cnt;
     const int32_t* list = ix.slots;
     if (!ix.use_slots) {
@@ -315,7 +317,14 @@ int launch_combine(const void* Xe, const float* G, const int32_t* I, void* Xout,
             hipLaunchKernelGGL((combine_kernel<TYPE, VECV, 16>), grid, block, 0, stream, (const TYPE*)Xe, G,  \
                                offs, list, (TYPE*)Xout, (int)n, (int)d, tpr, addend, src_rows);                                 \
     } while (0)
-    if (dtype == EC_BF16) EC_COMBINE_LAUNCH(bf16_t, 8, d / 8);
+    if (dtype == EC_BF16 && rows_f32) {
+        if (ix.use_slots) return EC_ERR_UNSUPPORTED;  // fp32 rows only come with the CSR lists (backward pass)
+        int tpr = pick_threads_per_row(d / 8);
+        long long blocks = ceil_div(n, 256 / tpr);
+        if (blocks > (1 << 20)) blocks = 1 << 20;
+        hipLaunchKernelGGL((combine_kernel<bf16_t, 8, 0, float>), dim3((unsigned)blocks), dim3(256), 0, stream,
+                           (const float*)Xe, G, offs, list, (bf16_t*)Xout, (int)n, (int)d, tpr, addend, src_rows);
+    } else if (dtype == EC_BF16) EC_COMBINE_LAUNCH(bf16_t, 8, d / 8);
     else if (d % 4 == 0) EC_COMBINE_LAUNCH(float, 4, d / 4);
     else EC_COMBINE_LAUNCH(float, 1, d);
 #undef EC_COMBINE_LAUNCH
