@@ -10,8 +10,6 @@ namespace ecmoe {
 static thread_local int g_last_hip_error = 0;
 void set_last_hip_error(hipError_t err) { g_last_hip_error = (int)err; }
 
-size_t topk_ws_bytes(int64_t n, int64_t e, int64_t k);  // topk.hip
-
 WsLayout ws_layout(int64_t n, int64_t d, int64_t e, int64_t k, int64_t d_ff, int dtype, int with_backward) {
     WsLayout L;
     const size_t es = elem_size(dtype);
@@ -32,7 +30,6 @@ WsLayout ws_layout(int64_t n, int64_t d, int64_t e, int64_t k, int64_t d_ff, int
     L.inv = take((size_t)e * k * 4);
     L.slot_cnt = take((size_t)n * 4);
     L.slots = take((size_t)n * COMBINE_SLOT_CAP * 4);
-    L.sortkeys = take(topk_ws_bytes(n, e, k));
     L.choice = take((size_t)n * 8 * 4);
     L.bwd = off;
     if (with_backward) take(bwd_ws_bytes(n, d, e, k, d_ff, dtype));
@@ -103,10 +100,8 @@ int ec_moe_gate(const void* X, const void* Wg, float* S, float* St, int64_t n, i
 int ec_moe_topk_tokens(const float* St, int64_t n, int64_t e, int64_t k, float* G, int32_t* I, void* ws,
                        size_t ws_bytes, void* stream) {
     if (!St || !G || !I || !sizes_ok(n, 1, e, k) || !all_aligned(St, G, I)) return EC_ERR_INVALID_ARG;
-    const size_t need = topk_ws_bytes(n, e, k);
-    if (!ws_ok(ws, ws_bytes, need)) return EC_ERR_WORKSPACE;
-    return launch_topk(St, n, e, k, G, I, need ? (unsigned long long*)ws : nullptr, nullptr, nullptr, 0, nullptr,
-                       (hipStream_t)stream);
+    (void)ws; (void)ws_bytes;  // the selection needs no scratch in global memory
+    return launch_topk(St, n, e, k, G, I, nullptr, nullptr, 0, nullptr, (hipStream_t)stream);
 }
 
 int ec_moe_topk_tokens_grouped(const float* St, int64_t n, int64_t e, int64_t groups, int64_t k_g, float* G,
@@ -116,7 +111,7 @@ int ec_moe_topk_tokens_grouped(const float* St, int64_t n, int64_t e, int64_t gr
         !all_aligned(St, G, I))
         return EC_ERR_INVALID_ARG;
     (void)ws; (void)ws_bytes;
-    return launch_topk(St, n, e, k_g, G, I, nullptr, nullptr, nullptr, 0, nullptr, (hipStream_t)stream, groups);
+    return launch_topk(St, n, e, k_g, G, I, nullptr, nullptr, 0, nullptr, (hipStream_t)stream, groups);
 }
 
 int ec_moe_dispatch(const void* X, const int32_t* I, void* Xin, int64_t n, int64_t d, int64_t e, int64_t k,
@@ -197,9 +192,8 @@ static int forward_impl(const void* X, const void* Wg, const void* W1, const voi
     const CombineIndex ix = combine_index_at(ws, L, e);
     int rc = launch_gate(X, Wg, S_out, St, n, d, e, dtype, combine_zero_ptr(ix), combine_zero_words(ix, n, e), st);
     if (rc != EC_OK) return rc;
-    rc = launch_topk(St, n, e, k_g, G, I, (unsigned long long*)at(ws, L.sortkeys),
-                     ix.use_slots ? ix.slot_cnt : nullptr, ix.slots, ix.slot_cap, ix.use_slots ? nullptr : ix.bitmap, st,
-                     groups);
+    rc = launch_topk(St, n, e, k_g, G, I, ix.use_slots ? ix.slot_cnt : nullptr, ix.slots, ix.slot_cap,
+                     ix.use_slots ? nullptr : ix.bitmap, st, groups);
     if (rc != EC_OK) return rc;
     // The bucket gather is fused into the first expert product unless the caller wants X_in itself.  With
     // identity experts X_e = X_in = the gathered rows of X: unless the caller asks for one of them, the
@@ -355,7 +349,7 @@ int ec_moe_forward_capped(const void* X, const void* Wg, const void* W1, const v
     rc = launch_capped_assignment(St, n, e, k, b, lambda, iters, A, solver, st);
     if (rc != EC_OK) return rc;
     // indices from TopK(A, k); the values it returns are entries of A and are replaced by the scores
-    rc = launch_topk(A, n, e, k, G, I, nullptr, ix.use_slots ? ix.slot_cnt : nullptr, ix.slots, ix.slot_cap,
+    rc = launch_topk(A, n, e, k, G, I, ix.use_slots ? ix.slot_cnt : nullptr, ix.slots, ix.slot_cap,
                      ix.use_slots ? nullptr : ix.bitmap, st);
     if (rc != EC_OK) return rc;
     rc = launch_gather_scores(St, I, G, n, e, k, st);

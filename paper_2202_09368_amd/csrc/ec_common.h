@@ -54,7 +54,6 @@ struct WsLayout {
     size_t inv;        // int32 [e*k]: bucket rows (i*k+j) grouped by token, expert-ascending
     size_t slot_cnt;   // int32 [n]: experts that chose a token                     (slot form, e <= COMBINE_SLOT_CAP)
     size_t slots;      // int32 [n, COMBINE_SLOT_CAP]: their bucket rows, arrival order
-    size_t sortkeys;   // uint64 [e, pow2(k)]: top-k sort staging when a bucket exceeds LDS
     size_t choice;     // int32 [8, n]: every token's chosen experts, rank-major (token-choice routing)
     size_t bwd;        // start of the backward-only region
     size_t total;
@@ -89,8 +88,8 @@ inline int64_t combine_zero_words(const CombineIndex& ix, int64_t n, int64_t e) 
 int launch_gate(const void* X, const void* Wg, float* S, float* St, int64_t n, int64_t d, int64_t e,
                 int dtype, uint32_t* zero_buf, int64_t zero_words, hipStream_t stream);
 int launch_topk(const float* St, int64_t n, int64_t e, int64_t k, float* G, int32_t* I,
-                unsigned long long* sortkeys_ws, int32_t* slot_cnt, int32_t* slots, int slot_cap, uint32_t* bitmap,
-                hipStream_t stream, int64_t groups = 1);
+                int32_t* slot_cnt, int32_t* slots, int slot_cap, uint32_t* bitmap, hipStream_t stream,
+                int64_t groups = 1);
 int launch_token_choice(const float* S, int64_t n, int64_t e, int64_t m, int64_t cap, float* G, int32_t* I,
                         int32_t* load, int32_t* choice_ws, int32_t* slot_cnt, int32_t* slots, int slot_cap,
                         uint32_t* bitmap, hipStream_t stream);

@@ -4,7 +4,9 @@
 // (n contiguous floats).  Scores are non-negative, so their bit patterns order
 // like unsigned integers, and (score bits, ~token) is a total order in which
 // "larger" means "admitted first".  Steps:
-//   1. stage the row in LDS when it fits (one HBM read), find min and max;
+//   1. read the row once and keep it on chip -- in the registers of the workgroup (rows up to 65536
+//      tokens, the kernel further down) or in LDS -- and find min and max; rows that fit neither are
+//      re-read from memory in every pass;
 //   2. radix-select on (bits - min), 8 bits per pass starting at the top bit of
 //      the actual range, until the bin holding the k-th score has at most
 //      TOPK_CAND_MAX members or all 32 bits are decided;
@@ -561,9 +563,6 @@ static size_t topk_lds_budget() {
     return budget;
 }
 
-// The selection needs no scratch in global memory.
-size_t topk_ws_bytes(int64_t, int64_t, int64_t) { return 0; }
-
 template <int R>
 static void launch_topk_reg(const float* St, int n_total, int n_seg, int k, int e, int groups, float* G, int32_t* I,
                             const TopkEmit& emit, hipStream_t stream) {
@@ -573,9 +572,7 @@ static void launch_topk_reg(const float* St, int n_total, int n_seg, int k, int 
 
 // n tokens in all, cut into `groups` equal segments; k is the bucket size per (expert, segment).
 int launch_topk(const float* St, int64_t n, int64_t e, int64_t k, float* G, int32_t* I,
-                unsigned long long* sortkeys_ws, int32_t* slot_cnt, int32_t* slots, int slot_cap, uint32_t* bitmap,
-                hipStream_t stream, int64_t groups) {
-    (void)sortkeys_ws;
+                int32_t* slot_cnt, int32_t* slots, int slot_cap, uint32_t* bitmap, hipStream_t stream, int64_t groups) {
     TopkEmit emit;
     emit.slot_cnt = slot_cnt; emit.slots = slots; emit.slot_cap = slot_cap;
     emit.bitmap = bitmap; emit.bitmap_words = (int)ceil_div(e, 32);
