@@ -260,39 +260,61 @@ def main() -> int:
         except Exception:
             threads = 1
         threads = min(threads, os.cpu_count() or threads)
-        # bounded sample: all n tokens through gate/TopK/dispatch/combine, the FFN on the first
-        # `se` experts (experts cost the same), scaled to the full expert count
-        se = e if d_ff == 0 else max(1, min(e, int(8 * (1024 * 768 * 3072) / max(1, k * d * d_ff))))
-        t0 = time.perf_counter()
-        S_o = ref.gate(inp["X"], inp["Wg"])
-        if capped:
-            A_o = ref.capped_assignment(S_o, k, capped, 1e-3, args.capped_iters)
-            _, I_o = ref.topk_tokens(np.ascontiguousarray(A_o.T), k)
-            G_o = np.stack([S_o[I_o[i], i] for i in range(e)])
-            Xin_o = ref.dispatch(inp["X"], I_o)
-        elif tc:
-            G_o, I_o, _ = ref.token_choice(S_o, tc, k)
-            Xin_o = ref.dispatch_padded(inp["X"], I_o)
-        else:
-            G_o, I_o = ref.topk_tokens(S_o, k) if groups == 1 else ref.topk_tokens_grouped(S_o, k_g, groups)
-            Xin_o = ref.dispatch(inp["X"], I_o)
-        t_route = time.perf_counter() - t0
-        t_ffn = 0.0
-        if d_ff:
+        # Bounded sample, about 10-30 s: whole passes over all n tokens for gate/TopK/dispatch/combine; the FFN
+        # on the first `se` experts (experts cost the same) scaled to the full expert count; for the
+        # forward+backward workload the oracle's FFN gradients on `sb` experts, scaled likewise.  Passes are
+        # repeated until 10 s have gone by (at most 12).
+        ffn_flops = 4.0 * e * k * d * d_ff
+        se = e if d_ff == 0 else max(1, min(e, int(e * 1.5e12 / max(ffn_flops, 1.0))))
+        sb = max(1, se // 4) if w.backward else 0
+        dY_h = wl.make_inputs(wl.scaled(w, d_ff=0), with_dy=True)["dY"] if w.backward else None
+
+        def one_pass():
             t0 = time.perf_counter()
-            Xe_s = ref.expert_ffn(Xin_o[:se], inp["W1"][:se], inp["W2"][:se], w.act)
-            t_ffn = (time.perf_counter() - t0) * (e / se)
-            Xe_o = np.concatenate([Xe_s] * ((e + se - 1) // se))[:e] if se < e else Xe_s
-        else:
-            Xe_o = Xin_o
-        t0 = time.perf_counter()
-        (ref.combine_padded if tc else ref.combine)(Xe_o, G_o, I_o, n)
-        t_comb = time.perf_counter() - t0
-        total = t_route + t_ffn + t_comb
-        cpu_baseline = {"value": round(n / total, 1), "unit": "tokens/s", "cores": int(threads), "kind": "oracle",
-                        "sample": (f"one pass over all {n} tokens for gate/TopK/dispatch/combine; expert FFN on "
-                                   f"{se} of {e} experts scaled x{e / se:g}; float64 numpy"),
-                        "seconds": round(total, 2)}
+            S_o = ref.gate(inp["X"], inp["Wg"])
+            if capped:
+                A_o = ref.capped_assignment(S_o, k, capped, 1e-3, args.capped_iters)
+                _, I_o = ref.topk_tokens(np.ascontiguousarray(A_o.T), k)
+                G_o = np.stack([S_o[I_o[i], i] for i in range(e)])
+                Xin_o = ref.dispatch(inp["X"], I_o)
+            elif tc:
+                G_o, I_o, _ = ref.token_choice(S_o, tc, k)
+                Xin_o = ref.dispatch_padded(inp["X"], I_o)
+            else:
+                G_o, I_o = ref.topk_tokens(S_o, k) if groups == 1 else ref.topk_tokens_grouped(S_o, k_g, groups)
+                Xin_o = ref.dispatch(inp["X"], I_o)
+            t = time.perf_counter() - t0
+            if d_ff:
+                t0 = time.perf_counter()
+                Xe_s = ref.expert_ffn(Xin_o[:se], inp["W1"][:se], inp["W2"][:se], w.act)
+                t += (time.perf_counter() - t0) * (e / se)
+                Xe_o = np.concatenate([Xe_s] * ((e + se - 1) // se))[:e] if se < e else Xe_s
+            else:
+                Xe_o = Xin_o
+            t0 = time.perf_counter()
+            (ref.combine_padded if tc else ref.combine)(Xe_o, G_o, I_o, n)
+            t += time.perf_counter() - t0
+            if w.backward:
+                t0 = time.perf_counter()
+                dXe_o, dG_o = ref.backward_combine(dY_h, Xe_o, G_o, I_o)
+                ref.backward_gate(inp["X"], inp["Wg"], S_o, dG_o, I_o)
+                t += time.perf_counter() - t0
+                t0 = time.perf_counter()
+                ref.backward_ffn(Xin_o[:sb], inp["W1"][:sb], inp["W2"][:sb], w.act, dXe_o[:sb])
+                t += (time.perf_counter() - t0) * (e / sb)
+            return t
+
+        total, passes, wall0 = 0.0, 0, time.perf_counter()
+        while passes < 12 and (passes == 0 or time.perf_counter() - wall0 < 10.0):
+            total += one_pass()
+            passes += 1
+        sample = f"{passes} pass(es) over all {n} tokens for gate/TopK/dispatch/combine"
+        if d_ff:
+            sample += f"; expert FFN on {se} of {e} experts" + (f" scaled x{e / se:g}" if se < e else "")
+        if w.backward:
+            sample += f"; FFN gradients on {sb} of {e} experts scaled x{e / sb:g}, gate and combine gradients in full"
+        cpu_baseline = {"value": round(passes * n / total, 1), "unit": "tokens/s", "cores": int(threads), "kind": "oracle",
+                        "sample": sample + "; float64 numpy", "seconds": round(time.perf_counter() - wall0, 2)}
 
     out = {
         "metric": "EC-MoE layer tokens/sec (1 GPU)", "value": round(tokens_per_s, 1), "unit": "tokens/s",
