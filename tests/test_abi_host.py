@@ -92,4 +92,30 @@ def test_invalid_arguments_are_rejected_on_the_host(m):
     assert fwd(P, None, 2.0, 1, P, 1 << 30) == INV
     assert fwd(P, P, 2.0, 1, None, 0) == WS
     assert fwd(P, P, 2.0, 1, P, 64) == WS
+    # grouped top-k: the groups must cut the tokens into equal runs; k_g within a run
+    assert lib.ec_moe_topk_tokens_grouped(P, 10, 2, 3, 1, P, P, None, 0, None) == INV
+    assert lib.ec_moe_topk_tokens_grouped(P, 12, 2, 0, 1, P, P, None, 0, None) == INV
+    assert lib.ec_moe_topk_tokens_grouped(P, 12, 2, 3, 5, P, P, None, 0, None) == INV
+    fwdg = lambda groups, ws, wsb: lib.ec_moe_forward_grouped(P, P, P, P, 2.0, groups, P, None, None, None, None,
+                                                              None, None, None, 64, 16, 4, 32, 1, 1, ws, wsb, None)
+    assert fwdg(3, P, 1 << 30) == INV           # 64 tokens do not split into 3 runs
+    assert fwdg(64, P, 1 << 30) == INV          # runs of one token: k_g = floor(1*2/4) = 0
+    assert fwdg(4, None, 0) == WS
+    # token choice: m within [1, min(e, 8)], buffers within [1, n], workspace of 32 n bytes
+    tc = lambda mm, cap, ws, wsb: lib.ec_moe_token_choice(P, 64, 4, mm, cap, P, P, None, ws, wsb, None)
+    assert tc(0, 16, P, 1 << 20) == INV
+    assert tc(5, 16, P, 1 << 20) == INV
+    assert tc(2, 0, P, 1 << 20) == INV
+    assert tc(2, 65, P, 1 << 20) == INV
+    assert tc(2, 16, P, 64) == WS
+    assert lib.ec_moe_forward_token_choice(P, P, P, P, 2.0, 9, P, None, None, None, None, None, None, 64, 16, 16, 32,
+                                           1, 1, P, 1 << 30, None) == INV
+    # capped expert choice: b and lambda positive and finite, a bounded sweep count, its own workspace
+    cap = lambda b, lam, iters, ws, wsb: lib.ec_moe_capped_assignment(P, 64, 4, 16, b, lam, iters, P, ws, wsb, None)
+    assert cap(0.0, 1e-3, 10, P, 1 << 30) == INV
+    assert cap(2.0, 0.0, 10, P, 1 << 30) == INV
+    assert cap(2.0, float("inf"), 10, P, 1 << 30) == INV
+    assert cap(2.0, 1e-3, -1, P, 1 << 30) == INV
+    assert cap(2.0, 1e-3, 10, P, 64) == WS
+    assert m.ec_moe_capped_workspace_bytes(0, 4) == 0 and m.ec_moe_capped_workspace_bytes(64, 4) >= 2 * 64 * 4 * 8
     assert m.ec_moe_last_hip_error() == 0      # nothing was launched
