@@ -41,8 +41,12 @@ token-choice routing against a hand-worked example, a per-token brute force,
 the dense top-m mixture when nothing is dropped, and its priority rule;
 the capped assignment of Sec. 3.3 against the linear programme solved by a
 library LP solver, the closed-form optimum when the cap is slack, and its
-constraints -- its projection formulas are a reading of the paper, which
-prints none: see the section's comment).
+constraints).
+parity partly unpinned: capped_assignment.  Its fixed point is pinned to the
+programme Sec. 3.3 prints, but the paper gives neither the projections nor
+what its "maximum of 100 iterations" return, so the iterate after a fixed
+number of sweeps follows this file's reading of the algorithm, not a printed
+one (see the section's comment).
 """
 from __future__ import annotations
 
