@@ -69,6 +69,7 @@ def test_capped_assignment(m, ref, n, e, k, b, lam, iters, scale):
     ("cfg2", dict(n=2048, d=256, e=16, d_ff=512), 2.0, 100),             # bf16
     ("cfg3", dict(n=2048, d=128, e=64, d_ff=256), 3.0, 60),
     ("cfg5", dict(n=4096, d=128, e=32), 1.0, 100),                       # identity experts
+    ("cfg2", dict(), 2.0, 100),                                          # full size, as `bench.py --capped 2` runs it
 ])
 def test_capped_forward(m, ref, base, kw, b, iters):
     w = wl.scaled(wl.WORKLOADS[base], **kw)

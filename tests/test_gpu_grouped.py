@@ -71,6 +71,7 @@ def test_grouped_topk_rejects_bad_groups(m):
     ("cfg2", dict(n=4096, d=256, e=16, d_ff=512), 8),                  # bf16, slot lists in the combine
     ("cfg3", dict(n=4096, d=128, e=64, d_ff=256), 16),                 # bf16, CSR index in the combine
     ("cfg5", dict(n=8192, d=128, e=32), 4),                            # identity experts
+    ("cfg2", dict(), 8),                                               # full size, as `bench.py --groups 8` runs it
 ])
 def test_grouped_forward(m, ref, base, kw, groups):
     w = wl.scaled(wl.WORKLOADS[base], **kw)

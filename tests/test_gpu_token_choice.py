@@ -95,6 +95,7 @@ def test_dispatch_and_combine_with_empty_rows(m, ref):
     ("cfg2", dict(n=4096, d=256, e=16, d_ff=512), 1, 1.0),
     ("cfg3", dict(n=4096, d=128, e=64, d_ff=256), 2, 2.0),              # bf16, CSR combine index
     ("cfg5", dict(n=8192, d=128, e=32), 2, 2.0),                        # identity experts, skewed tokens
+    ("cfg2", dict(), 2, 2.0),                                           # full size, as `bench.py --token-choice 2` runs it
 ])
 def test_token_choice_forward(m, ref, base, kw, m_top, c):
     w = wl.scaled(wl.WORKLOADS[base], c=c, **kw)
