@@ -126,12 +126,14 @@ gate_mfma_kernel(const bf16_t* __restrict__ X, const bf16_t* __restrict__ Wg, fl
 #pragma unroll
         for (int r = 0; r < 16; ++r) {
             int ex = te * 32 + 8 * (r >> 2) + 4 * half + (r & 3);
-            float p = ex < e ? expf(acc[te][r] - m) : 0.0f;
+            // exp through the hardware exp2 (relative 6e-8 * |z - max| from rounding the scaled argument)
+            float p = ex < e ? __builtin_amdgcn_exp2f((acc[te][r] - m) * 1.44269504088896340736f) : 0.0f;
             acc[te][r] = p;
             sum += p;
         }
     sum += __shfl_xor(sum, 32, kWave);
     if (tok >= n) return;
+    const float inv_sum = 1.0f / sum;
 #pragma unroll
     for (int te = 0; te < ET; ++te)
 #pragma unroll
@@ -139,7 +141,7 @@ gate_mfma_kernel(const bf16_t* __restrict__ X, const bf16_t* __restrict__ Wg, fl
             int ex0 = te * 32 + 8 * q + 4 * half;
             float v[4];
 #pragma unroll
-            for (int j = 0; j < 4; ++j) v[j] = acc[te][4 * q + j] / sum;
+            for (int j = 0; j < 4; ++j) v[j] = acc[te][4 * q + j] * inv_sum;
             if (ex0 >= e) continue;  // e % 8 == 0: a quad is all experts or all padding
             if (St != nullptr) {
 #pragma unroll

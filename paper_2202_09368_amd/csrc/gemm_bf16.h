@@ -355,7 +355,9 @@ gemm_bf16_kernel(const bf16_t* __restrict__ Aall, const bf16_t* __restrict__ Bal
 #pragma unroll
                 for (int r = 0; r < 16; ++r) {
                     const int ex = n0 + wc * WN + j * 32 + 8 * (r >> 2) + 4 * half + (r & 3);
-                    const float p = ex < N ? expf(acc[i][j][r] - mx[i]) : 0.0f;
+                    // exp through the hardware exp2: the rounding of (z - max) * log2(e) costs a relative
+                    // 6e-8 * |z - max|, far inside the tolerance of the scores wherever they are not negligible
+                    const float p = ex < N ? __builtin_amdgcn_exp2f((acc[i][j][r] - mx[i]) * 1.44269504088896340736f) : 0.0f;
                     acc[i][j][r] = p;
                     sum += p;
                 }
@@ -368,6 +370,7 @@ gemm_bf16_kernel(const bf16_t* __restrict__ Aall, const bf16_t* __restrict__ Bal
         for (int i = 0; i < TM; ++i) {
             const float other = xch[((wave ^ 1) * TM + i) * 32 + col];
             const float total_sum = part[i] + other;  // the same two addends in both wavefronts: the same sum
+            const float inv_sum = 1.0f / total_sum;    // one division per row, then multiplications
             const int gm = m0 + wr * WM + i * 32 + col;
             if (gm < M) {
 #pragma unroll
@@ -379,7 +382,7 @@ gemm_bf16_kernel(const bf16_t* __restrict__ Aall, const bf16_t* __restrict__ Bal
                             floatx4 o;
 #pragma unroll
                             for (int t = 0; t < 4; ++t) {
-                                o[t] = acc[i][j][4 * q + t] / total_sum;
+                                o[t] = acc[i][j][4 * q + t] * inv_sum;
                                 if (Ct != nullptr) Ct[(size_t)(ex0 + t) * M + gm] = o[t];
                             }
                             if (Cn != nullptr) *reinterpret_cast<floatx4*>(Cn + (size_t)gm * N + ex0) = o;
