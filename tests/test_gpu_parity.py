@@ -200,6 +200,8 @@ def test_cfg5_full_routing_only(m, ref):
     (128 * 256, 192, 256),
     (128 * 128 + 5, 256, 96),     # 65..128 experts: the 128-wide tile with padding columns
     (128 * 128, 64, 128),
+    (128 * 128 + 100, 128, 72),   # expert counts that are multiples of 8 only
+    (128 * 256, 64, 200),
 ])
 def test_gate_many_experts(m, ref, n, d, e):
     # shapes that take the matrix-product path of the gate (many experts, enough tokens to fill the chip)
