@@ -547,6 +547,82 @@ topk_tokens_reg_kernel(const float* __restrict__ St, int n_total, int n, int k, 
     }
 }
 
+// ---------------------------------------------------------------------------
+// Small segments (at most 256 tokens, a multiple of 4): one wavefront per (expert, segment), four scores
+// per lane, no LDS and no barrier -- the batched small selection that routing per group of tokens needs
+// when the groups are short (Limitations section: small batches at serving time).  The k-th largest
+// score is found bit by bit (31 counting steps with ballots: scores are non-negative floats), ties at
+// that score are admitted in token order, and the bucket is written in ascending token order.
+// ---------------------------------------------------------------------------
+__global__ void __launch_bounds__(256)
+topk_small_kernel(const float* __restrict__ St, int n_total, int n, int k, int e, int groups,
+                  float* __restrict__ G, int32_t* __restrict__ I, TopkEmit emit) {
+    const int lane = threadIdx.x & 63;
+    const long long job = (long long)blockIdx.x * 4 + (threadIdx.x >> 6);  // (expert, segment), segment fastest
+    if (job >= (long long)e * groups) return;                              // uniform per wavefront
+    const int expert = (int)(job / groups), group = (int)(job % groups);
+    const int tok0 = group * n;
+    const size_t out0 = (size_t)job * (size_t)k;
+    const unsigned int* __restrict__ colg = reinterpret_cast<const unsigned int*>(St) + (size_t)expert * n_total + tok0;
+    const unsigned long long lt_mask = (1ull << lane) - 1ull;
+    const bool valid = 4 * lane < n;  // n % 4 == 0: a lane's quad is inside or outside as a whole
+    unsigned int v[4] = {0u, 0u, 0u, 0u};
+    if (valid) {
+        const uint4 q = *reinterpret_cast<const uint4*>(colg + 4 * lane);
+        v[0] = q.x; v[1] = q.y; v[2] = q.z; v[3] = q.w;
+    }
+    auto count_ge = [&](unsigned int t) -> int {
+        int c = 0;
+#pragma unroll
+        for (int j = 0; j < 4; ++j) c += __popcll(__ballot(valid && v[j] >= t));
+        return c;
+    };
+    // largest T with at least k scores >= T: the k-th largest score
+    unsigned int T = 0u;
+    for (int bit = 30; bit >= 0; --bit) {
+        const unsigned int cand = T | (1u << bit);
+        if (count_ge(cand) >= k) T = cand;
+    }
+    int above = 0;
+#pragma unroll
+    for (int j = 0; j < 4; ++j) above += __popcll(__ballot(valid && v[j] > T));
+    const int need = k - above;  // ties at T to admit, lowest token indices first
+    // rank among the ties and position in the bucket, both in token order (lane-major, then element)
+    unsigned long long tie_bal[4];
+    int tie_before = 0;
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+        tie_bal[j] = __ballot(valid && v[j] == T);
+        tie_before += __popcll(tie_bal[j] & lt_mask);
+    }
+    bool sel[4];
+    int tr = tie_before;
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+        const bool tie = valid && v[j] == T;
+        sel[j] = valid && (v[j] > T || (tie && tr < need));
+        tr += tie ? 1 : 0;
+    }
+    int pos = 0;
+#pragma unroll
+    for (int j = 0; j < 4; ++j) pos += __popcll(__ballot(sel[j]) & lt_mask);
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+        if (sel[j] && pos < k) {  // pos < k always holds for a correct selection; guards the stores
+            const int tok = tok0 + 4 * lane + j;
+            G[out0 + pos] = __uint_as_float(v[j]);
+            I[out0 + pos] = tok;
+            if (emit.slot_cnt != nullptr) {
+                const int s = atomicAdd(&emit.slot_cnt[tok], 1);
+                if (s < emit.slot_cap) emit.slots[(size_t)tok * emit.slot_cap + s] = (int32_t)(out0 + pos);
+            }
+            if (emit.bitmap != nullptr)
+                atomicOr(&emit.bitmap[(size_t)tok * emit.bitmap_words + (expert >> 5)], 1u << (expert & 31));
+        }
+        pos += sel[j] ? 1 : 0;
+    }
+}
+
 // LDS the top-k kernel may use for the staged row.
 static size_t topk_lds_budget() {
     static size_t budget = 0;
@@ -577,6 +653,13 @@ int launch_topk(const float* St, int64_t n, int64_t e, int64_t k, float* G, int3
     emit.slot_cnt = slot_cnt; emit.slots = slots; emit.slot_cap = slot_cap;
     emit.bitmap = bitmap; emit.bitmap_words = (int)ceil_div(e, 32);
     const int64_t seg = n / groups;
+    if ((seg & 3) == 0 && seg <= 256 && e * groups >= 64) {
+        // many short segments: a wavefront each
+        const long long jobs = (long long)e * groups;
+        hipLaunchKernelGGL(topk_small_kernel, dim3((unsigned)((jobs + 3) / 4)), dim3(256), 0, stream, St, (int)n, (int)seg,
+                           (int)k, (int)e, (int)groups, G, I, emit);
+        return check_launch();
+    }
     if ((seg & 3) == 0 && seg <= 65536 && groups <= 65535) {
         // the row (segment) fits the registers of one workgroup: S^T is read once
         const int ni = (int)n, si = (int)seg, ki = (int)k, ei = (int)e, gi = (int)groups;

@@ -36,6 +36,10 @@ def _p(msg):
     (4000, 3, 10, 7, "const"),
     (65536 * 2, 2, 2, 300, "rand"),            # longest run the kernel accepts
     (16384, 4, 1, 512, "rand"),                # one group: the plain selection
+    (8192, 16, 64, 20, "rand"),                # short runs (128 tokens): one wavefront per (expert, group)
+    (4096, 8, 16, 256, "rand"),                # runs of 256 tokens, all of them taken
+    (2048, 64, 8, 3, "levels"), (2048, 64, 8, 200, "levels"), (1024, 128, 4, 100, "const"),
+    (240, 70, 1, 17, "rand"),                  # one short row per expert, the last lanes idle
 ])
 def test_grouped_topk(m, ref, n, e, groups, k_g, kind):
     _p(f"[grouped topk] n={n} e={e} groups={groups} k_g={k_g} {kind}")
@@ -72,6 +76,8 @@ def test_grouped_topk_rejects_bad_groups(m):
     ("cfg3", dict(n=4096, d=128, e=64, d_ff=256), 16),                 # bf16, CSR index in the combine
     ("cfg5", dict(n=8192, d=128, e=32), 4),                            # identity experts
     ("cfg2", dict(), 8),                                               # full size, as `bench.py --groups 8` runs it
+    ("cfg2", dict(n=4096, d=256, e=16, d_ff=512), 32),                 # runs of 128 tokens: the small-segment kernel
+    ("cfg3", dict(n=4096, d=128, e=64, d_ff=256), 64),
 ])
 def test_grouped_forward(m, ref, base, kw, groups):
     w = wl.scaled(wl.WORKLOADS[base], **kw)
