@@ -417,11 +417,14 @@ def forward_capped(X, Wg, W1, W2, c: float, act: int, b: float, lam: float = 1e-
 # ---------------------------------------------------------------- backward ---
 # The paper prints no backward pass.  These are the derivatives of Eq. 4, Eq. 3 and Eq. 2 in that
 # order, with the selection I a constant and the gate values G[i,j] = S[I[i,j], i] differentiable.
+# Buffers of token-choice routing may hold empty rows (I = -1): such a row took part in nothing, so
+# it receives no gradient and passes none on.
 def backward_combine(dY, X_e, G, I) -> Tuple[np.ndarray, np.ndarray]:
     """Eq. 4 differentiated: dX_e[i,j,:] = G[i,j] dY[I[i,j],:] and dG[i,j] = <dY[I[i,j],:], X_e[i,j,:]>."""
     dYd, Xed, Gd = widen(dY), widen(X_e), widen(G)
     Ii = np.asarray(I, dtype=np.int64)
-    dYsel = dYd[Ii, :]                                         # [e,k,d] rows of dY each bucket row fed
+    dYsel = dYd[np.maximum(Ii, 0), :]                          # [e,k,d] rows of dY each bucket row fed
+    dYsel[Ii < 0] = 0.0                                        # empty rows fed nothing
     dXe = Gd[:, :, None] * dYsel
     dG = np.einsum("ijt,ijt->ij", dYsel, Xed)
     return dXe, dG
@@ -455,7 +458,8 @@ def backward_gate(X, Wg, S, dG, I) -> Tuple[np.ndarray, np.ndarray, np.ndarray]:
     Ii = np.asarray(I, dtype=np.int64)
     dS = np.zeros((n, e), dtype=np.float64)
     for i in range(e):
-        dS[Ii[i], i] = dG[i]                                    # each token at most once per expert
+        filled = Ii[i] >= 0
+        dS[Ii[i][filled], i] = np.asarray(dG[i])[filled]        # each token at most once per expert
     dZ = Sd * (dS - (dS * Sd).sum(axis=1, keepdims=True))
     return Xd.T @ dZ, dZ @ Wgd.T, dZ
 
@@ -470,12 +474,14 @@ def backward(X, Wg, W1, W2, act: int, S: np.ndarray, G: np.ndarray, I: np.ndarra
     Ii = np.asarray(I, dtype=np.int64)
     n, d = np.asarray(X).shape
     e, k = Ii.shape
-    X_in = widen(X)[Ii, :]
+    X_in = widen(X)[np.maximum(Ii, 0), :]
+    X_in[Ii < 0] = 0.0                                          # empty rows gathered nothing
     X_e = expert_ffn(X_in, W1, W2, act)
     dXe, dG = backward_combine(dY, X_e, G, I)
     dXin, dW1, dW2 = backward_ffn(X_in, W1, W2, act, dXe)
     dWg, dX, dZ = backward_gate(X, Wg, S, dG, I)
     for i in range(e):
         for j in range(k):                                      # Eq. 3 gather differentiated: scatter-add
-            dX[Ii[i, j], :] += dXin[i, j, :]
+            if Ii[i, j] >= 0:
+                dX[Ii[i, j], :] += dXin[i, j, :]
     return {"dX": dX, "dWg": dWg, "dW1": dW1, "dW2": dW2, "dZ": dZ, "dG": dG}

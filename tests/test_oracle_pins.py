@@ -385,6 +385,50 @@ def test_backward_against_central_differences(act):
             assert abs(fd - g[name][idx]) <= 1e-6 * max(1.0, abs(fd)), (name, idx, fd, g[name][idx])
 
 
+def test_backward_with_empty_rows_against_central_differences():
+    # token-choice buffers: dropped tokens and empty rows; the routing (I) is held constant
+    r = _rng(31)
+    n, d, d_ff, e, m, cap = 14, 5, 6, 4, 2, 5
+    X = r.standard_normal((n, d))
+    Wg = r.standard_normal((d, e)) * 1.5
+    W1 = r.standard_normal((e, d, d_ff)) / math.sqrt(d)
+    W2 = r.standard_normal((e, d_ff, d)) / math.sqrt(d_ff)
+    dY = r.standard_normal((n, d))
+    S64 = ref.gate(X, Wg, out_dtype=np.float64)
+    _, I, load = ref.token_choice(S64.astype(np.float32), m, cap)
+    assert (I < 0).any() and (load > cap).any()            # both empty rows and drops occur
+    filled = I >= 0
+    G64 = np.where(filled, S64[np.maximum(I, 0), np.arange(e)[:, None]], 0.0)
+
+    def loss():
+        S = ref.gate(X, Wg, out_dtype=np.float64)
+        G = np.where(filled, S[np.maximum(I, 0), np.arange(e)[:, None]], 0.0)
+        X_e = ref.expert_ffn(ref.dispatch_padded(X, I), W1, W2, ref.ACT_GELU)
+        return float((ref.combine_padded(X_e, G, I, n) * dY).sum())
+
+    g = ref.backward(X, Wg, W1, W2, ref.ACT_GELU, S64, G64, I, dY)
+    h = 1e-6
+    for name, arr in (("dX", X), ("dWg", Wg), ("dW1", W1), ("dW2", W2)):
+        for _ in range(12):
+            idx = tuple(int(r.integers(0, s)) for s in arr.shape)
+            old = arr[idx]
+            arr[idx] = old + h
+            lp = loss()
+            arr[idx] = old - h
+            lm = loss()
+            arr[idx] = old
+            fd = (lp - lm) / (2 * h)
+            assert abs(fd - g[name][idx]) <= 1e-6 * max(1.0, abs(fd)), (name, idx, fd, g[name][idx])
+    # an expert whose buffer is entirely empty gets no weight gradient at all
+    S0 = S64.astype(np.float32).copy()
+    S0[:, 3] = 0.0
+    _, I0, _ = ref.token_choice(S0, 1, cap)
+    assert (I0[3] < 0).all()
+    G0 = np.where(I0 >= 0, S0[np.maximum(I0, 0), np.arange(e)[:, None]], 0.0)
+    g0 = ref.backward(X, Wg, W1, W2, ref.ACT_GELU, S0, G0, I0, dY)
+    assert (g0["dW1"][3] == 0).all() and (g0["dW2"][3] == 0).all()
+
+
 def test_backward_against_autograd_restatement():
     act = ref.ACT_GELU
     X, Wg, W1, W2, dY, S, G, I = _small_problem(23, act)
