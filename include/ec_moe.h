@@ -207,8 +207,11 @@ int ec_moe_forward_capped(const void* X, const void* Wg, const void* W1, const v
  * Outputs: dX [n,d] in `dtype`; dWg [d,e], dW1 [e,d,d_ff], dW2 [e,d_ff,d] float.
  * ws must come from ec_moe_workspace_bytes(..., with_backward = 1).
  * The pass depends on the routing only through S, G, I and the saved bucket tensors, so it also
- * serves ec_moe_forward_grouped (k = groups * k_g).  Every I[i,j] must lie in [0,n): the buffers
- * of token-choice routing, which may hold -1, are not supported here. */
+ * serves ec_moe_forward_grouped (k = groups * k_g) and the buffers of token-choice routing: an
+ * empty row (I = -1, with G = 0 and zero rows in X_in, A, H, X_e as the forward leaves them) gets
+ * and passes no gradient.  ec_moe_forward_token_choice has no A / H outputs: run the stages
+ * (ec_moe_gate, ec_moe_token_choice, ec_moe_dispatch, ec_moe_expert_ffn with A_save / H_save,
+ * ec_moe_combine) to keep what this pass needs. */
 int ec_moe_backward(const void* dY, const void* X, const void* Wg, const void* W1, const void* W2,
                     const float* S, const float* G, const int32_t* I,
                     const void* Xin, const void* A, const void* H, const void* Xe,

@@ -23,13 +23,14 @@ bwd_rows_kernel(const T* __restrict__ dY, const T* __restrict__ Xe, const float*
                 const int32_t* __restrict__ I, T* __restrict__ dXe, float* __restrict__ dG, long long rows, int d) {
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     for (long long r = (long long)blockIdx.x * 4 + wave; r < rows; r += (long long)gridDim.x * 4) {
-        const T* src = dY + (size_t)I[r] * d;
+        const int tok = I[r];  // -1: an empty buffer row (token-choice routing) fed nothing: zero gradient
+        const T* src = dY + (size_t)(tok < 0 ? 0 : tok) * d;
         const T* xe = Xe + (size_t)r * d;
         T* dst = dXe + (size_t)r * d;
         const float g = G[r];
         float dot = 0.0f;
         for (int t = lane; t < d; t += kWave) {
-            const float y = Cvt<T>::to_f32(src[t]);
+            const float y = tok < 0 ? 0.0f : Cvt<T>::to_f32(src[t]);
             dot = fmaf(y, Cvt<T>::to_f32(xe[t]), dot);
             dst[t] = Cvt<T>::from_f32(g * y);
         }

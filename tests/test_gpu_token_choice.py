@@ -137,3 +137,48 @@ def test_token_choice_forward(m, ref, base, kw, m_top, c):
     m.ec_moe_forward_token_choice(t["X"], t["Wg"], t.get("W1"), t.get("W2"), c, m_top, Xout2, w.act, ws)
     torch.cuda.synchronize()
     assert (to_host(Xout2) == to_host(Xout)).all()
+
+
+@pytest.mark.parametrize("base,kw,tol", [
+    ("cfg1", dict(n=256, d=64, e=8, c=2.0, d_ff=128, act=wl.ACT_GELU), 2e-4),
+    ("cfg2", dict(n=2048, d=256, e=16, d_ff=512), 2e-2),
+    ("cfg3", dict(n=4096, d=256, e=32, d_ff=512), 2e-2),        # CSR combine index, many empty rows and drops
+])
+def test_token_choice_backward(m, ref, base, kw, tol):
+    # forward stage by stage (the saved activations come from ec_moe_expert_ffn), then ec_moe_backward on
+    # buffers with dropped tokens and empty rows, against the oracle's backward on the same routing
+    w = wl.scaled(wl.WORKLOADS[base], backward=True, **kw)
+    inp = wl.make_inputs(w)
+    n, d, e, f = w.n, w.d, w.e, w.d_ff
+    cap = ref.capacity(n, w.c, e)
+    dt = torch_dtype(w)
+    t = {key: to_dev(inp[key]) for key in ("X", "Wg", "W1", "W2", "dY")}
+    ws = m.alloc_workspace(n, d, e, cap, f, w.dtype, with_backward=True)
+    dev = dict(device="cuda")
+    S = torch.empty((n, e), dtype=torch.float32, **dev)
+    G = torch.empty((e, cap), dtype=torch.float32, **dev)
+    I = torch.empty((e, cap), dtype=torch.int32, **dev)
+    load = torch.empty((e,), dtype=torch.int32, **dev)
+    Xin = torch.empty((e, cap, d), dtype=dt, **dev)
+    A = torch.empty((e, cap, f), dtype=dt, **dev)
+    H = torch.empty((e, cap, f), dtype=dt, **dev)
+    Xe = torch.empty((e, cap, d), dtype=dt, **dev)
+    m.ec_moe_gate(t["X"], t["Wg"], S, None, None)
+    m.ec_moe_token_choice(S, 2, cap, G, I, load, ws)
+    m.ec_moe_dispatch(t["X"], I, Xin)
+    m.ec_moe_expert_ffn(Xin, t["W1"], t["W2"], Xe, w.act, ws, A_save=A, H_save=H)
+    dX = torch.empty((n, d), dtype=dt, **dev)
+    dWg = torch.empty((d, e), dtype=torch.float32, **dev)
+    dW1 = torch.empty((e, d, f), dtype=torch.float32, **dev)
+    dW2 = torch.empty((e, f, d), dtype=torch.float32, **dev)
+    m.ec_moe_backward(t["dY"], t["X"], t["Wg"], t["W1"], t["W2"], S, G, I, Xin, A, H, Xe, dX, dWg, dW1, dW2, w.act, ws)
+    torch.cuda.synchronize()
+    I_h = to_host(I)
+    _p(f"[token choice backward] {base} n={n} e={e} cap={cap}: empty rows {(I_h < 0).sum()}, "
+       f"dropped {int(to_host(load).sum() - (I_h >= 0).sum())}")
+    assert (I_h < 0).any()
+    g = ref.backward(inp["X"], inp["Wg"], inp["W1"], inp["W2"], w.act, to_host(S), to_host(G), I_h, inp["dY"])
+    for key, got in (("dX", dX), ("dWg", dWg), ("dW1", dW1), ("dW2", dW2)):
+        err = max_rel_err(to_host(got), g[key])
+        _p(f"[token choice backward] {key} max rel err {err:.3e}")
+        assert err <= (1.5 * tol if key == "dX" else tol)
