@@ -17,25 +17,33 @@ namespace ecmoe {
 // ---------------------------------------------------------------------------
 // dX_e and dG: one wavefront per bucket row.
 // ---------------------------------------------------------------------------
-template <typename T>
+template <typename T, int VEC>
 __global__ void __launch_bounds__(256)
 bwd_rows_kernel(const T* __restrict__ dY, const T* __restrict__ Xe, const float* __restrict__ G,
                 const int32_t* __restrict__ I, T* __restrict__ dXe, float* __restrict__ dG, long long rows, int d) {
+    typedef T vec_t __attribute__((ext_vector_type(VEC)));  // VEC elements = 16 bytes when the rows allow it
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int nvec = d / VEC;
     for (long long r = (long long)blockIdx.x * 4 + wave; r < rows; r += (long long)gridDim.x * 4) {
         const int tok = I[r];  // -1: an empty buffer row (token-choice routing) fed nothing: zero gradient
-        const T* src = dY + (size_t)(tok < 0 ? 0 : tok) * d;
-        const T* xe = Xe + (size_t)r * d;
-        T* dst = dXe + (size_t)r * d;
-        const float g = G[r];
+        const vec_t* src = reinterpret_cast<const vec_t*>(dY + (size_t)(tok < 0 ? 0 : tok) * d);
+        const vec_t* xe = reinterpret_cast<const vec_t*>(Xe + (size_t)r * d);
+        vec_t* dst = reinterpret_cast<vec_t*>(dXe + (size_t)r * d);
+        const float g = tok < 0 ? 0.0f : G[r];
         float dot = 0.0f;
-        for (int t = lane; t < d; t += kWave) {
-            const float y = tok < 0 ? 0.0f : Cvt<T>::to_f32(src[t]);
-            dot = fmaf(y, Cvt<T>::to_f32(xe[t]), dot);
-            dst[t] = Cvt<T>::from_f32(g * y);
+        for (int t = lane; t < nvec; t += kWave) {
+            const vec_t y = src[t], x = xe[t];
+            vec_t o;
+#pragma unroll
+            for (int q = 0; q < VEC; ++q) {
+                const float yf = Cvt<T>::to_f32(y[q]);
+                dot = fmaf(yf, Cvt<T>::to_f32(x[q]), dot);
+                o[q] = Cvt<T>::from_f32(g * yf);
+            }
+            dst[t] = o;
         }
         dot = wave_reduce_sum(dot);
-        if (lane == 0) dG[r] = dot;
+        if (lane == 0) dG[r] = tok < 0 ? 0.0f : dot;
     }
 }
 
@@ -280,7 +288,13 @@ static int backward_typed(const T* dY, const T* X, const T* Wg, const T* W1, con
     {
         long long blocks = ceil_div(rows, 4);
         if (blocks > (1 << 20)) blocks = 1 << 20;
-        hipLaunchKernelGGL(bwd_rows_kernel<T>, dim3((unsigned)blocks), dim3(256), 0, stream, dY, Xe, G, I, dXe, dG, rows, D);
+        constexpr int V16 = 16 / (int)sizeof(T);
+        if (d % V16 == 0)
+            hipLaunchKernelGGL((bwd_rows_kernel<T, V16>), dim3((unsigned)blocks), dim3(256), 0, stream, dY, Xe, G, I, dXe, dG,
+                               rows, D);
+        else
+            hipLaunchKernelGGL((bwd_rows_kernel<T, 1>), dim3((unsigned)blocks), dim3(256), 0, stream, dY, Xe, G, I, dXe, dG,
+                               rows, D);
     }
     // Eq. 3 backwards
     if (mfma) {

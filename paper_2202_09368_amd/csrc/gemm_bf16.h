@@ -105,14 +105,18 @@ gemm_bf16_kernel(const bf16_t* __restrict__ Aall, const bf16_t* __restrict__ Bal
     bf16_t* smem = reinterpret_cast<bf16_t*>(smem_raw);
 
     // XCD-aware tile order: workgroups are handed to the 8 XCDs round-robin, so give each XCD a
-    // contiguous run of logical tiles; consecutive logical tiles share the N-side panel (m fastest),
-    // which then stays in that XCD's L2.
+    // contiguous run of logical tiles; consecutive logical tiles share an operand panel, which then
+    // stays in that XCD's L2.
     const int total = G * tiles_m * tiles_n;
     const int per_xcd = (total + 7) / 8;
     const int logical = (blockIdx.x & 7) * per_xcd + (blockIdx.x >> 3);
     if (EPI != EPI_SOFTMAX && logical >= total) return;
-    const int tm = logical % tiles_m;
-    const int tn = (logical / tiles_m) % tiles_n;
+    // the axis with fewer tiles varies fastest, so that the 32 tiles an XCD works on at a time span all of the
+    // short axis and a few panels of the long one: both operands' panels then fit its L2 and are read from
+    // HBM once (a tall product walked m-first re-read its whole M-side operand for every column of tiles)
+    const bool n_fast = tiles_m > tiles_n;
+    const int tm = n_fast ? (logical / tiles_n) % tiles_m : logical % tiles_m;
+    const int tn = n_fast ? logical % tiles_n : (logical / tiles_m) % tiles_n;
     const int g = logical / (tiles_m * tiles_n);
     const int m0 = tm * BM, n0 = tn * BN;
 
