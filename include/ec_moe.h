@@ -169,10 +169,12 @@ int ec_moe_token_choice(const float* S, int64_t n, int64_t e, int64_t m, int64_t
  * with cap = floor(n*c/e) (Eq. 1: with c = m the buffers match expert choice at equal cost, the
  * comparison of Sec. 3.4), dispatch, expert FFN, combine with the raw scores as weights.
  * Optional outputs, NULL to skip: S_out [n,e], G_out / I_out [e,cap], load_out [e],
- * Xin_out / Xe_out [e,cap,d].  Workspace: ec_moe_workspace_bytes with k = cap.  Forward only. */
+ * Xin_out / Xe_out [e,cap,d], A_out / H_out [e,cap,d_ff] -- with k = cap they are what
+ * ec_moe_backward consumes.  Workspace: ec_moe_workspace_bytes with k = cap. */
 int ec_moe_forward_token_choice(const void* X, const void* Wg, const void* W1, const void* W2,
                                 double c, int64_t m, void* Xout, float* S_out, float* G_out,
-                                int32_t* I_out, int32_t* load_out, void* Xin_out, void* Xe_out,
+                                int32_t* I_out, int32_t* load_out, void* Xin_out, void* A_out,
+                                void* H_out, void* Xe_out,
                                 int64_t n, int64_t d, int64_t e, int64_t d_ff, int act, int dtype,
                                 void* ws, size_t ws_bytes, void* stream);
 
@@ -209,9 +211,7 @@ int ec_moe_forward_capped(const void* X, const void* Wg, const void* W1, const v
  * The pass depends on the routing only through S, G, I and the saved bucket tensors, so it also
  * serves ec_moe_forward_grouped (k = groups * k_g) and the buffers of token-choice routing: an
  * empty row (I = -1, with G = 0 and zero rows in X_in, A, H, X_e as the forward leaves them) gets
- * and passes no gradient.  ec_moe_forward_token_choice has no A / H outputs: run the stages
- * (ec_moe_gate, ec_moe_token_choice, ec_moe_dispatch, ec_moe_expert_ffn with A_save / H_save,
- * ec_moe_combine) to keep what this pass needs. */
+ * and passes no gradient. */
 int ec_moe_backward(const void* dY, const void* X, const void* Wg, const void* W1, const void* W2,
                     const float* S, const float* G, const int32_t* I,
                     const void* Xin, const void* A, const void* H, const void* Xe,

@@ -50,7 +50,7 @@ _SIGNATURES = {
     "ec_moe_forward_grouped": (c_int, [_P, _P, _P, _P, c_double, _I64, _P, _P, _P, _P, _P, _P, _P, _P,
                                        _I64, _I64, _I64, _I64, c_int, c_int, _P, _SZ, _P]),
     "ec_moe_token_choice": (c_int, [_P, _I64, _I64, _I64, _I64, _P, _P, _P, _P, _SZ, _P]),
-    "ec_moe_forward_token_choice": (c_int, [_P, _P, _P, _P, c_double, _I64, _P, _P, _P, _P, _P, _P, _P,
+    "ec_moe_forward_token_choice": (c_int, [_P, _P, _P, _P, c_double, _I64, _P, _P, _P, _P, _P, _P, _P, _P, _P,
                                             _I64, _I64, _I64, _I64, c_int, c_int, _P, _SZ, _P]),
     "ec_moe_capped_workspace_bytes": (c_size_t, [_I64, _I64]),
     "ec_moe_capped_assignment": (c_int, [_P, _I64, _I64, _I64, c_double, c_double, _I64, _P, _P, _SZ, _P]),
@@ -218,7 +218,7 @@ def ec_moe_token_choice(S, m: int, cap: int, G, I, load, ws) -> None:
 
 
 def ec_moe_forward_token_choice(X, Wg, W1, W2, c: float, m: int, Xout, act: int, ws, S_out=None, G_out=None,
-                                I_out=None, load_out=None, Xin_out=None, Xe_out=None) -> None:
+                                I_out=None, load_out=None, Xin_out=None, A_out=None, H_out=None, Xe_out=None) -> None:
     n, d = X.shape
     e = Wg.shape[1]
     d_ff = W1.shape[2] if W1 is not None else 0
@@ -227,7 +227,7 @@ def ec_moe_forward_token_choice(X, Wg, W1, W2, c: float, m: int, Xout, act: int,
     _check("ec_moe_forward_token_choice", lib().ec_moe_forward_token_choice(
         _ptr(X), _ptr(Wg, dt), _ptr(W1, dt), _ptr(W2, dt), c, m, _ptr(Xout, dt), _ptr(S_out, torch.float32),
         _ptr(G_out, torch.float32), _ptr(I_out, torch.int32), _ptr(load_out, torch.int32), _ptr(Xin_out, dt),
-        _ptr(Xe_out, dt), n, d, e, d_ff, act, _dtype_code(X), wp, wb, _stream()))
+        _ptr(A_out, dt), _ptr(H_out, dt), _ptr(Xe_out, dt), n, d, e, d_ff, act, _dtype_code(X), wp, wb, _stream()))
 
 
 def ec_moe_capped_workspace_bytes(n: int, e: int) -> int:

@@ -249,13 +249,13 @@ int ec_moe_token_choice(const float* S, int64_t n, int64_t e, int64_t m, int64_t
 
 int ec_moe_forward_token_choice(const void* X, const void* Wg, const void* W1, const void* W2, double c, int64_t m,
                                 void* Xout, float* S_out, float* G_out, int32_t* I_out, int32_t* load_out,
-                                void* Xin_out, void* Xe_out, int64_t n, int64_t d, int64_t e, int64_t d_ff, int act,
-                                int dtype, void* ws, size_t ws_bytes, void* stream) {
+                                void* Xin_out, void* A_out, void* H_out, void* Xe_out, int64_t n, int64_t d, int64_t e,
+                                int64_t d_ff, int act, int dtype, void* ws, size_t ws_bytes, void* stream) {
     int64_t k = 0;  // rows of an expert's buffer
     if (ec_moe_capacity(n, e, c, &k) != EC_OK || m < 1 || m > e || m > 8) return EC_ERR_INVALID_ARG;
     const bool identity = (W1 == nullptr && W2 == nullptr);
     if (!X || !Wg || !Xout || !sizes_ok(n, d, e, k) || !dtype_ok(dtype) || !act_ok(act) || !width_ok(d, dtype) ||
-        !all_aligned(X, Wg, W1, W2, Xout, S_out, G_out, I_out, load_out, Xin_out, Xe_out))
+        !all_aligned(X, Wg, W1, W2, Xout, S_out, G_out, I_out, load_out, Xin_out, A_out, H_out, Xe_out))
         return EC_ERR_INVALID_ARG;
     if (identity) {
         if (act != EC_ACT_IDENTITY) return EC_ERR_INVALID_ARG;
@@ -288,8 +288,8 @@ int ec_moe_forward_token_choice(const void* X, const void* Wg, const void* W1, c
     const void* Xe = Xin;
     if (!identity) {
         void* Xe_w = Xe_out ? Xe_out : at(ws, L.xe);
-        rc = launch_ffn(fused_gather ? nullptr : Xin, X, I, n, W1, W2, Xe_w, nullptr, at(ws, L.h), e, k, d, d_ff, act,
-                        dtype, st);
+        rc = launch_ffn(fused_gather ? nullptr : Xin, X, I, n, W1, W2, Xe_w, A_out, H_out ? H_out : at(ws, L.h), e, k, d,
+                        d_ff, act, dtype, st);
         if (rc != EC_OK) return rc;
         Xe = Xe_w;
     }

@@ -108,8 +108,8 @@ def test_invalid_arguments_are_rejected_on_the_host(m):
     assert tc(2, 0, P, 1 << 20) == INV
     assert tc(2, 65, P, 1 << 20) == INV
     assert tc(2, 16, P, 64) == WS
-    assert lib.ec_moe_forward_token_choice(P, P, P, P, 2.0, 9, P, None, None, None, None, None, None, 64, 16, 16, 32,
-                                           1, 1, P, 1 << 30, None) == INV
+    assert lib.ec_moe_forward_token_choice(P, P, P, P, 2.0, 9, P, None, None, None, None, None, None, None, None, 64, 16,
+                                           16, 32, 1, 1, P, 1 << 30, None) == INV
     # capped expert choice: b and lambda positive and finite, a bounded sweep count, its own workspace
     cap = lambda b, lam, iters, ws, wsb: lib.ec_moe_capped_assignment(P, 64, 4, 16, b, lam, iters, P, ws, wsb, None)
     assert cap(0.0, 1e-3, 10, P, 1 << 30) == INV

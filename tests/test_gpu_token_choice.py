@@ -145,8 +145,8 @@ def test_token_choice_forward(m, ref, base, kw, m_top, c):
     ("cfg3", dict(n=4096, d=256, e=32, d_ff=512), 2e-2),        # CSR combine index, many empty rows and drops
 ])
 def test_token_choice_backward(m, ref, base, kw, tol):
-    # forward stage by stage (the saved activations come from ec_moe_expert_ffn), then ec_moe_backward on
-    # buffers with dropped tokens and empty rows, against the oracle's backward on the same routing
+    # the forward keeps what the backward consumes; ec_moe_backward then runs on buffers with dropped tokens
+    # and empty rows, against the oracle's backward on the same routing
     w = wl.scaled(wl.WORKLOADS[base], backward=True, **kw)
     inp = wl.make_inputs(w)
     n, d, e, f = w.n, w.d, w.e, w.d_ff
@@ -163,10 +163,9 @@ def test_token_choice_backward(m, ref, base, kw, tol):
     A = torch.empty((e, cap, f), dtype=dt, **dev)
     H = torch.empty((e, cap, f), dtype=dt, **dev)
     Xe = torch.empty((e, cap, d), dtype=dt, **dev)
-    m.ec_moe_gate(t["X"], t["Wg"], S, None, None)
-    m.ec_moe_token_choice(S, 2, cap, G, I, load, ws)
-    m.ec_moe_dispatch(t["X"], I, Xin)
-    m.ec_moe_expert_ffn(Xin, t["W1"], t["W2"], Xe, w.act, ws, A_save=A, H_save=H)
+    Xout = torch.empty((n, d), dtype=dt, **dev)
+    m.ec_moe_forward_token_choice(t["X"], t["Wg"], t["W1"], t["W2"], w.c, 2, Xout, w.act, ws, S_out=S, G_out=G, I_out=I,
+                                  load_out=load, Xin_out=Xin, A_out=A, H_out=H, Xe_out=Xe)
     dX = torch.empty((n, d), dtype=dt, **dev)
     dWg = torch.empty((d, e), dtype=torch.float32, **dev)
     dW1 = torch.empty((e, d, f), dtype=torch.float32, **dev)
