@@ -79,16 +79,8 @@ def test_backward_reduced(m, ref, name, kw, tol):
 
 
 def _progress(msg):
-    """Progress of the long full-size test, to stdout and to a file a watcher can see grow."""
-    line = f"[cfg4 {time.strftime('%H:%M:%S')}] {msg}"
-    print(line, flush=True)
-    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
-    try:
-        os.makedirs(os.path.join(root, "gpurun_out"), exist_ok=True)
-        with open(os.path.join(root, "gpurun_out", "cfg4_full_progress.log"), "a") as f:
-            f.write(line + "\n")
-    except OSError:
-        pass
+    """Progress of the long full-size test (it runs for most of a minute)."""
+    print(f"[cfg4 {time.strftime('%H:%M:%S')}] {msg}", flush=True)
 
 
 def test_cfg4_full_forward_backward(m, ref):
