@@ -126,6 +126,21 @@ int ec_moe_combine(const void* Xe, const float* G, const int32_t* I, void* Xout,
                    int64_t n, int64_t d, int64_t e, int64_t k, int dtype,
                    void* ws, size_t ws_bytes, void* stream);
 
+/* ec_moe_combine for callers that cannot allocate or pass a workspace: code under HIP graph
+ * capture, tight serving loops, harnesses that forbid hipMalloc.  Same inputs, outputs, arithmetic
+ * and order of additions as ec_moe_combine (bit-identical X_out); the token-major index is built in
+ * a static device array of EC_MOE_STATIC_SCRATCH_BYTES inside the library (one copy per GPU, held
+ * until the process ends) instead of in `ws`.  Nothing is allocated or freed, no memset is enqueued
+ * (the index is cleared by a fill kernel).
+ * Limit: the index must fit the array -- e <= 16: 4*n*(1 + cap) bytes with cap = 4, 8 or 16 slots
+ * (the smallest that holds e); e > 16: 4*n*ceil(e/32) + 4*(n+1) + 4*e*k + 4096 bytes, each part rounded up
+ * to 256.  Larger problems return EC_ERR_UNSUPPORTED and enqueue nothing.
+ * All calls on one GPU share the array, which keeps the previous call's contents: calls that overlap
+ * on one GPU (different streams, or threads without ordering) race; order them on one stream. */
+#define EC_MOE_STATIC_SCRATCH_BYTES (8u << 20)
+int ec_moe_combine_static(const void* Xe, const float* G, const int32_t* I, void* Xout,
+                          int64_t n, int64_t d, int64_t e, int64_t k, int dtype, void* stream);
+
 /* Sec. 3.2, Eq. 1-4 in one call on one stream: gate, TopK over tokens,
  * dispatch, expert FFN, combine.  k = floor(n*c/e) as in ec_moe_capacity.
  * W1 = W2 = NULL with act = EC_ACT_IDENTITY runs identity experts (routing

@@ -44,6 +44,7 @@ _SIGNATURES = {
     "ec_moe_dispatch": (c_int, [_P, _P, _P, _I64, _I64, _I64, _I64, c_int, _P]),
     "ec_moe_expert_ffn": (c_int, [_P, _P, _P, _P, _P, _P, _I64, _I64, _I64, _I64, c_int, c_int, _P, _SZ, _P]),
     "ec_moe_combine": (c_int, [_P, _P, _P, _P, _I64, _I64, _I64, _I64, c_int, _P, _SZ, _P]),
+    "ec_moe_combine_static": (c_int, [_P, _P, _P, _P, _I64, _I64, _I64, _I64, c_int, _P]),
     "ec_moe_forward": (c_int, [_P, _P, _P, _P, c_double, _P, _P, _P, _P, _P, _P, _P, _P,
                                _I64, _I64, _I64, _I64, c_int, c_int, _P, _SZ, _P]),
     "ec_moe_topk_tokens_grouped": (c_int, [_P, _I64, _I64, _I64, _I64, _P, _P, _P, _SZ, _P]),
@@ -174,6 +175,14 @@ def ec_moe_combine(Xe, G, I, Xout, ws) -> None:
     _check("ec_moe_combine", lib().ec_moe_combine(_ptr(Xe), _ptr(G, torch.float32), _ptr(I, torch.int32),
                                                   _ptr(Xout, Xe.dtype), n, d, e, k, _dtype_code(Xe), wp, wb,
                                                   _stream()))
+
+
+def ec_moe_combine_static(Xe, G, I, Xout) -> None:
+    e, k, d = Xe.shape
+    n = Xout.shape[0]
+    _check("ec_moe_combine_static", lib().ec_moe_combine_static(
+        _ptr(Xe), _ptr(G, torch.float32), _ptr(I, torch.int32), _ptr(Xout, Xe.dtype), n, d, e, k, _dtype_code(Xe),
+        _stream()))
 
 
 def ec_moe_forward(X, Wg, W1, W2, c: float, Xout, act: int, ws, S_out=None, G_out=None, I_out=None,

@@ -160,6 +160,14 @@ int ec_moe_combine(const void* Xe, const float* G, const int32_t* I, void* Xout,
     return launch_combine(Xe, G, I, Xout, n, d, e, k, dtype, ix, (hipStream_t)stream);
 }
 
+int ec_moe_combine_static(const void* Xe, const float* G, const int32_t* I, void* Xout, int64_t n, int64_t d,
+                          int64_t e, int64_t k, int dtype, void* stream) {
+    if (!Xe || !G || !I || !Xout || !sizes_ok(n, d, e, k) || !dtype_ok(dtype) || !width_ok(d, dtype) ||
+        !all_aligned(Xe, G, I, Xout))
+        return EC_ERR_INVALID_ARG;
+    return combine_static(Xe, G, I, Xout, n, d, e, k, dtype, (hipStream_t)stream);
+}
+
 // The layer with TopK taken inside each of `groups` equal runs of tokens (groups = 1: Eq. 2 as printed).
 static int forward_impl(const void* X, const void* Wg, const void* W1, const void* W2, double c, int64_t groups,
                         void* Xout, float* S_out, float* G_out, int32_t* I_out, void* Xin_out, void* A_out,

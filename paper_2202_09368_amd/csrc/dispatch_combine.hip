@@ -4,9 +4,15 @@
 // combine:  X_out[l,:] = sum_{(i,j): I[i,j]=l} G[i,j] X_e[i,j,:], deterministic.
 //   A token-major index is built from I with integer atomics only (see below); one group of
 //   lanes per token then adds that token's bucket rows in ascending expert order in fp32.
+#include <mutex>
+
 #include "ec_common.h"
 
 namespace ecmoe {
+
+// Scratch of ec_moe_combine_static: the token-major index lives here instead of in a caller's
+// workspace.  One copy per GPU, held until the process ends; every call on a GPU shares it.
+static __device__ __align__(256) unsigned char scratch[EC_MOE_STATIC_SCRATCH_BYTES];
 
 // ------------------------------------------------------------------ dispatch
 // One row per group of `tpr` threads; each thread moves 16 bytes per step.
@@ -329,6 +335,61 @@ int launch_combine(const void* Xe, const float* G, const int32_t* I, void* Xout,
     else EC_COMBINE_LAUNCH(float, 1, d);
 #undef EC_COMBINE_LAUNCH
     return check_launch();
+}
+
+// Eq. 4 with the token-major index in the library's own static device array (nothing is allocated).
+// The array's device address is looked up once per GPU, with that GPU current; host code only ever
+// uses that address, never the array's name.
+int combine_static(const void* Xe, const float* G, const int32_t* I, void* Xout, int64_t n, int64_t d, int64_t e,
+                   int64_t k, int dtype, hipStream_t stream) {
+    constexpr int MAX_DEVICES = 64;
+    static std::mutex mu;
+    static unsigned char* scratch_ptr[MAX_DEVICES] = {};
+    int dev = -1;
+    hipError_t err = hipGetDevice(&dev);
+    if (err != hipSuccess || dev < 0 || dev >= MAX_DEVICES) {
+        set_last_hip_error(err != hipSuccess ? err : hipErrorInvalidDevice);
+        return EC_ERR_HIP;
+    }
+    unsigned char* base;
+    {
+        std::lock_guard<std::mutex> lock(mu);
+        if (scratch_ptr[dev] == nullptr) {
+            void* p = nullptr;
+            err = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+            if (err != hipSuccess || p == nullptr) {
+                set_last_hip_error(err != hipSuccess ? err : hipErrorInvalidSymbol);
+                return EC_ERR_HIP;
+            }
+            scratch_ptr[dev] = static_cast<unsigned char*>(p);
+        }
+        base = scratch_ptr[dev];
+    }
+    // carve-up: only the form of the index that this expert count uses
+    CombineIndex ix;
+    ix.use_slots = e <= COMBINE_SLOT_CAP;
+    ix.slot_cap = e <= 4 ? 4 : e <= 8 ? 8 : 16;
+    size_t off = 0;
+    auto take = [&](size_t bytes) { size_t a = off; off = align_up(off + bytes, 256); return a; };
+    size_t o_cnt, o_slots = 0, o_bitmap = 0, o_offsets = 0, o_inv = 0;
+    if (ix.use_slots) {
+        o_cnt = take((size_t)n * 4);
+        o_slots = take((size_t)n * ix.slot_cap * 4);
+    } else {
+        o_cnt = take(1024 * 4);  // totals of the scan blocks (at most 1024 of them)
+        o_bitmap = take((size_t)n * (size_t)ceil_div(e, 32) * 4);
+        o_offsets = take((size_t)(n + 1) * 4);
+        o_inv = take((size_t)e * k * 4);
+    }
+    if (off > (size_t)EC_MOE_STATIC_SCRATCH_BYTES) return EC_ERR_UNSUPPORTED;
+    ix.slot_cnt = reinterpret_cast<int32_t*>(base + o_cnt);
+    ix.slots = reinterpret_cast<int32_t*>(base + o_slots);
+    ix.bitmap = reinterpret_cast<uint32_t*>(base + o_bitmap);
+    ix.offsets = reinterpret_cast<int32_t*>(base + o_offsets);
+    ix.inv = reinterpret_cast<int32_t*>(base + o_inv);
+    int rc = launch_combine_index(I, n, e, k, ix, stream);  // clears the counters / bitmap with a fill kernel first
+    if (rc != EC_OK) return rc;
+    return launch_combine(Xe, G, I, Xout, n, d, e, k, dtype, ix, stream);
 }
 
 }  // namespace ecmoe

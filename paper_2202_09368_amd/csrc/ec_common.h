@@ -111,6 +111,8 @@ int launch_combine(const void* Xe, const float* G, const int32_t* I, void* Xout,
                    int64_t e, int64_t k, int dtype, const CombineIndex& ix, hipStream_t stream,
                    const float* addend = nullptr, bool csr_ready = false, const int32_t* src_rows = nullptr,
                    bool rows_f32 = false);
+int combine_static(const void* Xe, const float* G, const int32_t* I, void* Xout, int64_t n, int64_t d, int64_t e,
+                   int64_t k, int dtype, hipStream_t stream);
 int launch_backward(const void* dY, const void* X, const void* Wg, const void* W1, const void* W2,
                     const float* S, const float* G, const int32_t* I, const void* Xin, const void* A,
                     const void* H, const void* Xe, void* dX, float* dWg, float* dW1, float* dW2,
