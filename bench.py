@@ -1,23 +1,30 @@
 #!/usr/bin/env python3
-"""Benchmark of the expert-choice MoE layer forward on one MI355X.
+"""Benchmark of the expert-choice MoE layer on one MI355X.  Prints ONE JSON line.
 
-A step is one ec_moe_forward call (gate -> TopK over tokens -> dispatch ->
-expert FFN -> combine) on the "cfg2" workload: the paper's 0.1B/16E layer
-(Table 1: d=768, d_ff=3072, 16 experts) at capacity factor 2 over 8192 tokens,
-bf16 with fp32 accumulation, seeded synthetic Gaussian inputs already resident
-in HBM.  Prints ONE JSON line.
+Headline (default): the largest single-GPU workload, "cfg4" -- forward + backward of the layer over
+32768 tokens, d=2048, 128 experts, capacity factor 2 (k=512), GeLU FFN with d_ff=8192, bf16 with fp32
+accumulation and fp32 weight gradients.  A step is one ec_moe_forward call that keeps what the backward
+consumes, followed by one ec_moe_backward call; seeded synthetic Gaussian inputs are resident in HBM
+before the timed region starts.  The other bf16 workloads (cfg2 = the paper's 0.1B/16E layer of
+Table 1, cfg3, cfg5 = routing only) are timed the same way and reported under "workloads".
 
-Timed region 1 (the headline `value`): K back-to-back ec_moe_forward calls.
-Timed region 2 (for `roofline` and `stages`): the same K steps issued stage by
-stage through the C ABI with HIP events between the stages on the launch
-stream, so each kernel's own duration is measured live.
-The CPU oracle is timed on the host for the `cpu_baseline` leg.
+Per workload:
+  region 1 (`value`, `ms_per_step`): K back-to-back steps bracketed by synchronisations;
+  region 2 (`stages`, `roofline`): the same K steps issued stage by stage through the C ABI with HIP
+    events on the launch stream between the stages (the backward through ec_moe_backward_timed, which
+    records its own events between its kernels), so every kernel's duration is measured live.
+`roofline` describes the workload's dominant kernel; its `traffic` is read at run time from the
+rocprofv3 FETCH_SIZE / WRITE_SIZE summary of the same workload under profiles/ (null if absent).
+`context` holds the vendor library's (torch.bmm -> hipBLASLt) time for the same products on the same
+box: a calibration of what dense bf16 reaches here, not part of the product path.
+`cpu_baseline`: the float64 oracle timed on the host cores on a bounded sample of the headline workload.
 """
 from __future__ import annotations
 
 import argparse
 import json
 import os
+import re
 import sys
 import time
 
@@ -27,20 +34,18 @@ if ROOT not in sys.path:
 
 PEAK_HBM_GBS = 8000.0          # MI355X HBM3E, published
 PEAK_BF16_TFLOPS = 2500.0      # MI355X dense bf16 MFMA, published
-
-# HBM bytes per expert-GEMM launch (mean of the two launches of one FFN call) from the rocprofv3
-# --pmc FETCH_SIZE / WRITE_SIZE runs summarised in profiles/cfg2_forward_hbm_traffic.txt
-# (first product 114.47 MiB read + 96.00 MiB written, second 172.19 + 24.00); None where not measured.
-MEASURED_FFN_TRAFFIC_BYTES = {"cfg2": int((114.47 + 96.00 + 172.19 + 24.00) * 1048576 / 2)}
+HEADLINE = "cfg4"
+OTHERS = ("cfg2", "cfg3", "cfg5")
 
 
 def parse_args():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=50)
-    ap.add_argument("--warmup", type=int, default=10)
-    ap.add_argument("--workload", default="cfg2",
-                    help="cfg2 (headline), cfg3, cfg5 (routing only), cfg4 (forward + backward)")
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--workload", default="all",
+                    help="all (default): cfg4 forward+backward as the headline, cfg2/cfg3/cfg5 under 'workloads'; "
+                         "or one of cfg2, cfg3, cfg4, cfg5 alone (what the rocprofv3 summaries are taken on)")
     ap.add_argument("--groups", type=int, default=1,
                     help="expert choice inside this many equal runs of tokens (1: the paper's global TopK)")
     ap.add_argument("--token-choice", type=int, default=0, metavar="M",
@@ -51,58 +56,56 @@ def parse_args():
                          "--capped-iters Dykstra sweeps at lambda = 0.001")
     ap.add_argument("--capped-iters", type=int, default=100)
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-context", action="store_true", help="skip the vendor-library calibration")
     ap.add_argument("--copy-calibration", type=int, default=0, metavar="MiB",
                     help="only run a plain device-to-device copy of this many MiB five times (reference "
                          "reading for the FETCH_SIZE / WRITE_SIZE counters) and exit")
     return ap.parse_args()
 
 
-def main() -> int:
-    args = parse_args()
-    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
-        print("bench.py: this build measures the layer on ONE GPU only (no sharding, no collectives); "
-              "run with --gpus 1", file=sys.stderr)
-        return 2
+def read_traffic(workload: str, kernel_prefixes):
+    """HBM bytes per launch (read + written, mean over the named kernels' dispatches) from the rocprofv3 summary
+    profiles/<workload>_*hbm_traffic.txt; None when the file or a kernel is missing."""
+    pdir = os.path.join(ROOT, "profiles")
+    try:
+        names = [f for f in os.listdir(pdir) if f.startswith(workload + "_") and f.endswith("hbm_traffic.txt")]
+    except OSError:
+        return None
+    if not names:
+        return None
+    rows = []
+    for line in open(os.path.join(pdir, sorted(names)[0])):
+        mt = re.match(r"\s+(\S.*?)\s+(\d+)\s+([\d.]+)\s+([\d.]+)\s*$", line)
+        if mt and not line.startswith("#"):
+            rows.append((mt.group(1), int(mt.group(2)), float(mt.group(3)), float(mt.group(4))))
+    total, launches = 0.0, 0
+    for prefix in kernel_prefixes:
+        hit = [r for r in rows if r[0].startswith(prefix)]
+        if not hit:
+            return None
+        for _, disp, rd, wr in hit:
+            total += disp * (rd + wr) * 1048576.0
+            launches += disp
+    return int(total / launches) if launches else None
 
-    import numpy as np
-    import torch
 
-    import paper_2202_09368_amd as m
-    import workloads as wl
-
-    if not torch.cuda.is_available():
-        print("bench.py: no GPU visible", file=sys.stderr)
-        return 2
-    m.lib()  # fails loudly when the HIP library is missing
-
-    if args.copy_calibration > 0:
-        nbytes = args.copy_calibration << 20
-        src = torch.ones(nbytes, dtype=torch.uint8, device="cuda")
-        dst = torch.empty_like(src)
-        for _ in range(5):
-            dst.copy_(src)
-        torch.cuda.synchronize()
-        print(json.dumps({"copy_calibration_bytes": nbytes, "copies": 5}))
-        return 0
-
-    w = wl.WORKLOADS[args.workload]
-    n, d, e, k, d_ff = w.n, w.d, w.e, w.k, w.d_ff
-    groups = args.groups
+def run_workload(args, m, wl, torch, np, name: str, variants: bool, cpu_baseline: bool):
+    """Times one workload; returns (record, context_inputs)."""
+    w = wl.WORKLOADS[name]
+    n, d, e, d_ff = w.n, w.d, w.e, w.d_ff
+    groups = args.groups if variants else 1
+    tc = args.token_choice if variants else 0
+    capped = args.capped if variants else 0.0
     if groups < 1 or n % groups != 0 or (groups > 1 and w.backward):
-        print("bench.py: --groups must divide the token count (forward workloads only)", file=sys.stderr)
-        return 2
-    tc = args.token_choice
+        raise SystemExit("bench.py: --groups must divide the token count (forward workloads only)")
     if tc and (groups > 1 or w.backward or not (1 <= tc <= min(e, 8))):
-        print("bench.py: --token-choice M needs a forward workload, one group and 1 <= M <= min(e, 8)", file=sys.stderr)
-        return 2
-    capped = args.capped
+        raise SystemExit("bench.py: --token-choice M needs a forward workload, one group and 1 <= M <= min(e, 8)")
     if capped and (tc or groups > 1 or w.backward):
-        print("bench.py: --capped needs a forward workload, one group and no --token-choice", file=sys.stderr)
-        return 2
+        raise SystemExit("bench.py: --capped needs a forward workload, one group and no --token-choice")
     k_g = m.ec_moe_capacity(n // groups, e, w.c)
     k = groups * k_g          # rows of an expert's bucket (groups = 1: Eq. 1)
     b = 2 if w.dtype == wl.DTYPE_BF16 else 4
-    inp = wl.make_inputs(w, with_dy=False)
+    inp = wl.make_inputs(w, with_dy=w.backward)
 
     def dev(a):
         if a.dtype == np.uint16:
@@ -113,7 +116,8 @@ def main() -> int:
     W1 = dev(inp["W1"]) if d_ff else None
     W2 = dev(inp["W2"]) if d_ff else None
     dt = X.dtype
-    ws = m.alloc_workspace(n, d, e, k, d_ff, w.dtype)
+    f32 = torch.float32
+    ws = m.alloc_workspace(n, d, e, k, d_ff, w.dtype, with_backward=w.backward)
     if capped:   # the layer's regions, then the solver's state, then A
         ws = torch.empty(ws.numel() + m.ec_moe_capped_workspace_bytes(n, e) + (4 * e * n + 255) // 256 * 256,
                          dtype=torch.uint8, device="cuda")
@@ -121,11 +125,10 @@ def main() -> int:
     K, W = args.steps, args.warmup
 
     # ---- timed region 1: whole layer ----------------------------------------
+    sv = gr = dY = None
     if w.backward:
         # forward + backward workload: the forward keeps what the backward consumes
-        f32 = torch.float32
-        dY = dev(wl.make_inputs(wl.scaled(w, d_ff=0), with_dy=True)["dY"])
-        ws = m.alloc_workspace(n, d, e, k, d_ff, w.dtype, with_backward=True)
+        dY = dev(inp["dY"])
         sv = dict(S=torch.empty((n, e), dtype=f32, device="cuda"), G=torch.empty((e, k), dtype=f32, device="cuda"),
                   I=torch.empty((e, k), dtype=torch.int32, device="cuda"),
                   Xin=torch.empty((e, k, d), dtype=dt, device="cuda"), A=torch.empty((e, k, d_ff), dtype=dt, device="cuda"),
@@ -161,19 +164,20 @@ def main() -> int:
     tokens_per_s = n / (ms_per_step * 1e-3)
 
     # ---- timed region 2: stage by stage with HIP events ---------------------
-    St = torch.empty((e, n), dtype=torch.float32, device="cuda")
-    G = torch.empty((e, k), dtype=torch.float32, device="cuda")
-    I = torch.empty((e, k), dtype=torch.int32, device="cuda")
-    Xin = torch.empty((e, k, d), dtype=dt, device="cuda")
-    Xe = torch.empty((e, k, d), dtype=dt, device="cuda") if d_ff else Xin
-    names = ["gate"] + (["capped_assignment"] if capped else []) + ["topk", "dispatch"] + (["expert_ffn"] if d_ff else []) + ["combine"]
-
-    Acap = torch.empty((e, n), dtype=torch.float32, device="cuda") if capped else None
+    St = torch.empty((e, n), dtype=f32, device="cuda")
+    Sn = sv["S"] if w.backward else (torch.empty((n, e), dtype=f32, device="cuda") if tc else None)
+    G = sv["G"] if w.backward else torch.empty((e, k), dtype=f32, device="cuda")
+    I = sv["I"] if w.backward else torch.empty((e, k), dtype=torch.int32, device="cuda")
+    Xin = sv["Xin"] if w.backward else torch.empty((e, k, d), dtype=dt, device="cuda")
+    Xe = (sv["Xe"] if w.backward else torch.empty((e, k, d), dtype=dt, device="cuda")) if d_ff else Xin
+    names = (["gate"] + (["capped_assignment"] if capped else []) + ["topk", "dispatch"]
+             + (["expert_ffn"] if d_ff else []) + ["combine"])
+    Acap = torch.empty((e, n), dtype=f32, device="cuda") if capped else None
     wscap = torch.empty(m.ec_moe_capped_workspace_bytes(n, e), dtype=torch.uint8, device="cuda") if capped else None
-    Sn = torch.empty((n, e), dtype=torch.float32, device="cuda") if tc else None
     load = torch.empty((e,), dtype=torch.int32, device="cuda") if tc else None
+    bwd_ms = {}
 
-    def staged_step(events):
+    def staged_step(events, timed):
         events[0].record()
         m.ec_moe_gate(X, Wg, Sn, None if tc else St, ws)
         events[1].record()
@@ -193,24 +197,35 @@ def main() -> int:
         events[j0 + 1].record()
         j = j0 + 1
         if d_ff:
-            m.ec_moe_expert_ffn(Xin, W1, W2, Xe, w.act, ws)
+            if w.backward:
+                m.ec_moe_expert_ffn(Xin, W1, W2, Xe, w.act, ws, A_save=sv["A"], H_save=sv["H"])
+            else:
+                m.ec_moe_expert_ffn(Xin, W1, W2, Xe, w.act, ws)
             j += 1
             events[j].record()
         m.ec_moe_combine(Xe, G, I, Xout, ws)
         events[j + 1].record()
+        if w.backward:
+            ms = m.ec_moe_backward_timed(dY, X, Wg, W1, W2, sv["S"], G, I, Xin, sv["A"], sv["H"], Xe,
+                                         gr["dX"], gr["dWg"], gr["dW1"], gr["dW2"], w.act, ws)
+            if timed:
+                for key, v in ms.items():
+                    bwd_ms[key] = bwd_ms.get(key, 0.0) + v
 
     # the FFN's hidden buffer and the combine index share the workspace start in the stage-wise
     # calls; the stages run in order on one stream, so that is safe
     ev = [[torch.cuda.Event(enable_timing=True) for _ in range(len(names) + 1)] for _ in range(K)]
     warm = [torch.cuda.Event(enable_timing=True) for _ in range(len(names) + 1)]
-    for _ in range(max(W, 1)):
-        staged_step(warm)
+    for _ in range(max(min(W, 3), 1)):
+        staged_step(warm, False)
     torch.cuda.synchronize()
     for s in range(K):
-        staged_step(ev[s])
+        staged_step(ev[s], True)
     torch.cuda.synchronize()
     stage_us = {nm: sum(ev[s][j].elapsed_time(ev[s][j + 1]) for s in range(K)) * 1e3 / K
                 for j, nm in enumerate(names)}
+    for key, v in bwd_ms.items():
+        stage_us[key] = v * 1e3 / K
 
     alg_bytes = {
         # per sweep: the row sums read the state once, the column/box step reads and writes both arrays
@@ -219,40 +234,57 @@ def main() -> int:
         "topk": n * e * 4 + 8 * e * k,
         "dispatch": 2 * e * k * d * b + 4 * e * k,
         "combine": e * k * d * b + n * d * b + 8 * e * k,
+        # backward stages that move bytes rather than multiply: dX_e written, dY gathered and X_e read, dG written
+        "bwd_rows": 3 * e * k * d * b + 8 * e * k,
+        "bwd_index": 8 * e * k + 4 * n * ((e + 31) // 32) + 4 * (n + 1),
+        "bwd_dZ": 3 * n * e * 4 + 4 * e * k,
+        "bwd_scatter": e * k * d * 4 + n * d * 4 + n * d * b + 8 * e * k,
     }
+    gemm = 2.0 * e * k * d * d_ff      # flop of one grouped expert product (all experts)
+    alg_flops = {"expert_ffn": 2 * gemm, "bwd_dW2": gemm, "bwd_dA": gemm, "bwd_dW1": gemm, "bwd_dX_in": gemm,
+                 "bwd_gate_products": 4.0 * n * d * e}
     stages = {}
-    for nm in names:
-        us = stage_us[nm]
+    for nm, us in stage_us.items():
         entry = {"us": round(us, 2)}
-        if nm == "expert_ffn":
-            flops = 4.0 * e * k * d * d_ff
-            entry.update(flop=flops, tflops=round(flops / (us * 1e-6) / 1e12, 2),
-                         frac_of_mfma_peak=round(flops / (us * 1e-6) / 1e12 / PEAK_BF16_TFLOPS, 4))
+        if nm in alg_flops:
+            tf = alg_flops[nm] / (us * 1e-6) / 1e12
+            entry.update(flop=alg_flops[nm], tflops=round(tf, 2), frac_of_mfma_peak=round(tf / PEAK_BF16_TFLOPS, 4))
         else:
             gbs = alg_bytes[nm] / (us * 1e-6) / 1e9
             entry.update(bytes=alg_bytes[nm], gbs=round(gbs, 1), frac_of_hbm_peak=round(gbs / PEAK_HBM_GBS, 4))
         stages[nm] = entry
 
-    if d_ff:
+    if w.backward:
+        # dominant kernel: the weight-gradient product (dW2 = H^T dX_e and dW1 = X_in^T dA: two launches of the
+        # grouped MFMA GEMM with both operands token-indexed and fp32 output), 2*e*k*d*d_ff flop per launch
+        avg_launch_s = (stage_us["bwd_dW2"] + stage_us["bwd_dW1"]) * 1e-6 / 2.0
+        achieved = gemm / avg_launch_s / 1e12
+        kernel = "gemm_bf16_kernel<256, 256, 2, 1, true, false, 3, 2"
+        roofline = {"kernel": kernel + ", false> (weight gradients dW2, dW1: 2 launches per step)", "bound": "mfma",
+                    "achieved": round(achieved, 2), "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
+                    "frac": round(achieved / PEAK_BF16_TFLOPS, 4), "avg_launch_us": round(avg_launch_s * 1e6, 2),
+                    "flop_per_launch": gemm, "traffic": read_traffic(w.name, [kernel])}
+    elif d_ff:
         # dominant kernel: the grouped bf16 MFMA GEMM, launched twice per FFN call (X_in.W1, H.W2),
         # 2*e*k*d*d_ff flop per launch
-        flop_per_launch = 2.0 * e * k * d * d_ff
         avg_launch_s = stage_us["expert_ffn"] * 1e-6 / 2.0
-        achieved = flop_per_launch / avg_launch_s / 1e12
+        achieved = gemm / avg_launch_s / 1e12
         roofline = {"kernel": "gemm_bf16_kernel (grouped expert GEMM, 2 launches per FFN)", "bound": "mfma",
                     "achieved": round(achieved, 2), "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
                     "frac": round(achieved / PEAK_BF16_TFLOPS, 4),
-                    "avg_launch_us": round(avg_launch_s * 1e6, 2),
-                    "traffic": MEASURED_FFN_TRAFFIC_BYTES.get(w.name)}
+                    "avg_launch_us": round(avg_launch_s * 1e6, 2), "flop_per_launch": gemm,
+                    "traffic": read_traffic(w.name, ["gemm_bf16_kernel<"])}
     else:
         nm = max(("dispatch", "combine", "gate"), key=lambda s: stage_us[s])
         gbs = alg_bytes[nm] / (stage_us[nm] * 1e-6) / 1e9
+        prefix = {"dispatch": "dispatch_kernel", "combine": "combine_kernel", "gate": "gemm_bf16_kernel"}[nm]
         roofline = {"kernel": nm, "bound": "hbm", "achieved": round(gbs, 1), "peak": PEAK_HBM_GBS, "unit": "GB/s",
-                    "frac": round(gbs / PEAK_HBM_GBS, 4), "avg_launch_us": round(stage_us[nm], 2), "traffic": None}
+                    "frac": round(gbs / PEAK_HBM_GBS, 4), "avg_launch_us": round(stage_us[nm], 2),
+                    "bytes_per_launch": alg_bytes[nm], "traffic": read_traffic(w.name, [prefix])}
 
     # ---- CPU oracle on the host cores ---------------------------------------
-    cpu_baseline = None
-    if not args.no_cpu_baseline:
+    cpu = None
+    if cpu_baseline:
         from oracle import ec_moe_ref as ref
         try:
             from threadpoolctl import threadpool_info
@@ -267,7 +299,6 @@ def main() -> int:
         ffn_flops = 4.0 * e * k * d * d_ff
         se = e if d_ff == 0 else max(1, min(e, int(e * 1.5e12 / max(ffn_flops, 1.0))))
         sb = max(1, se // 4) if w.backward else 0
-        dY_h = wl.make_inputs(wl.scaled(w, d_ff=0), with_dy=True)["dY"] if w.backward else None
 
         def one_pass():
             t0 = time.perf_counter()
@@ -296,7 +327,7 @@ def main() -> int:
             t += time.perf_counter() - t0
             if w.backward:
                 t0 = time.perf_counter()
-                dXe_o, dG_o = ref.backward_combine(dY_h, Xe_o, G_o, I_o)
+                dXe_o, dG_o = ref.backward_combine(inp["dY"], Xe_o, G_o, I_o)
                 ref.backward_gate(inp["X"], inp["Wg"], S_o, dG_o, I_o)
                 t += time.perf_counter() - t0
                 t0 = time.perf_counter()
@@ -313,14 +344,12 @@ def main() -> int:
             sample += f"; expert FFN on {se} of {e} experts" + (f" scaled x{e / se:g}" if se < e else "")
         if w.backward:
             sample += f"; FFN gradients on {sb} of {e} experts scaled x{e / sb:g}, gate and combine gradients in full"
-        cpu_baseline = {"value": round(passes * n / total, 1), "unit": "tokens/s", "cores": int(threads), "kind": "oracle",
-                        "sample": sample + "; float64 numpy", "seconds": round(time.perf_counter() - wall0, 2)}
+        cpu = {"value": round(passes * n / total, 1), "unit": "tokens/s", "cores": int(threads), "kind": "oracle",
+               "sample": sample + "; float64 numpy", "seconds": round(time.perf_counter() - wall0, 2)}
 
-    out = {
-        "metric": "EC-MoE layer tokens/sec (1 GPU)", "value": round(tokens_per_s, 1), "unit": "tokens/s",
-        "n_gpus": 1, "steps": K, "warmup": W, "ms_per_step": round(ms_per_step, 4),
-        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
-        "dtype": "bf16" if w.dtype == wl.DTYPE_BF16 else "f32", "data": "synthetic",
+    rec = {
+        "value": round(tokens_per_s, 1), "unit": "tokens/s", "ms_per_step": round(ms_per_step, 4),
+        "dtype": "bf16" if w.dtype == wl.DTYPE_BF16 else "f32",
         "config": {"workload": f"{w.name}: EC-MoE layer forward{' + backward' if w.backward else ''}, "
                                f"n={n} d={d} e={e} c={w.c:g} k={k} d_ff={d_ff}"
                                + (f", TopK inside {groups} groups of {n // groups} tokens" if groups > 1 else "")
@@ -328,16 +357,126 @@ def main() -> int:
                                + (f", at most {capped:g} experts per token (lambda=0.001, {args.capped_iters} sweeps)"
                                   if capped else ""),
                    "act": {0: "relu", 1: "gelu", 2: "identity"}[w.act], "seed": w.seed},
-        "roofline": roofline, "cpu_baseline": cpu_baseline, "stages": stages,
+        "roofline": roofline, "stages": stages,
     }
+    if w.backward:
+        flop_step = 6 * gemm + 6.0 * n * d * e     # two forward and four backward expert products, three gate products
+        rec["step_tflops"] = round(flop_step / (ms_per_step * 1e-3) / 1e12, 1)
+    if cpu is not None:
+        rec["cpu_baseline"] = cpu
     if tc:
         # the load imbalance Sec. 3.1 describes, on this synthetic gate: tokens per expert before dropping
         ld = load.cpu().numpy().astype(np.int64)
         placed = int((I.cpu().numpy() >= 0).sum())
-        out["routing"] = {"kind": f"token-choice top-{tc}", "buffer_rows": int(k),
+        rec["routing"] = {"kind": f"token-choice top-{tc}", "buffer_rows": int(k),
                           "max_over_capacity_ratio": round(float(ld.max()) / k - 1.0, 4),
                           "dropped_fraction": round(1.0 - placed / float(n * tc), 4),
                           "empty_buffer_rows": int(e * k - placed)}
+    return rec
+
+
+def vendor_context(torch, wl, names):
+    """torch.bmm (hipBLASLt) on the expert products of the named workloads, random bf16 data: what the vendor's
+    dense bf16 GEMM reaches on this machine for the same shapes.  Harness only; the product path never calls it."""
+    def timed(fn, reps=5):
+        fn()
+        torch.cuda.synchronize()
+        a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        a.record()
+        for _ in range(reps):
+            fn()
+        b.record()
+        torch.cuda.synchronize()
+        return a.elapsed_time(b) * 1e3 / reps   # us
+
+    out = {"library": "torch.bmm / torch.mm (hipBLASLt), bf16 in, bf16 out", "products": {}}
+    g = torch.Generator(device="cuda").manual_seed(7)
+    bf = torch.bfloat16
+
+    def rnd(*shape):
+        return torch.randn(*shape, generator=g, device="cuda", dtype=torch.float32).to(bf)
+
+    for name in names:
+        w = wl.WORKLOADS[name]
+        if not w.d_ff:
+            continue
+        e, k, d, f = w.e, w.k, w.d, w.d_ff
+        flop = 2.0 * e * k * d * f
+        Xin, W1, H, W2 = rnd(e, k, d), rnd(e, d, f), rnd(e, k, f), rnd(e, f, d)
+        prods = {"X_in.W1": lambda: torch.bmm(Xin, W1), "H.W2": lambda: torch.bmm(H, W2)}
+        if w.backward:
+            dXe = rnd(e, k, d)
+            Ht = H.transpose(1, 2)
+            prods["H^T.dX_e (weight gradient, bf16 output where the layer writes fp32)"] = lambda: torch.bmm(Ht, dXe)
+        for label, fn in prods.items():
+            us = timed(fn)
+            out["products"][f"{name} {label}"] = {"us": round(us, 1), "tflops": round(flop / us / 1e6, 1),
+                                                  "frac_of_mfma_peak": round(flop / us / 1e6 / PEAK_BF16_TFLOPS, 4)}
+        del Xin, W1, H, W2
+        torch.cuda.empty_cache()
+    A, B = rnd(8192, 8192), rnd(8192, 8192)
+    us = timed(lambda: torch.mm(A, B))
+    out["products"]["dense 8192^3"] = {"us": round(us, 1), "tflops": round(2.0 * 8192 ** 3 / us / 1e6, 1),
+                                       "frac_of_mfma_peak": round(2.0 * 8192 ** 3 / us / 1e6 / PEAK_BF16_TFLOPS, 4)}
+    return out
+
+
+def main() -> int:
+    args = parse_args()
+    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
+        print("bench.py: this build measures the layer on ONE GPU only (no sharding, no collectives); "
+              "run with --gpus 1", file=sys.stderr)
+        return 2
+
+    import numpy as np
+    import torch
+
+    import paper_2202_09368_amd as m
+    import workloads as wl
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        return 2
+    m.lib()  # fails loudly when the HIP library is missing
+
+    if args.copy_calibration > 0:
+        nbytes = args.copy_calibration << 20
+        src = torch.ones(nbytes, dtype=torch.uint8, device="cuda")
+        dst = torch.empty_like(src)
+        for _ in range(5):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        print(json.dumps({"copy_calibration_bytes": nbytes, "copies": 5}))
+        return 0
+
+    single = args.workload != "all"
+    if single and args.workload not in wl.WORKLOADS:
+        print(f"bench.py: unknown workload {args.workload}", file=sys.stderr)
+        return 2
+    if not single and (args.groups != 1 or args.token_choice or args.capped):
+        print("bench.py: the routing variants need --workload cfgN", file=sys.stderr)
+        return 2
+    head_name = args.workload if single else HEADLINE
+    head = run_workload(args, m, wl, torch, np, head_name, variants=single, cpu_baseline=not args.no_cpu_baseline)
+    torch.cuda.empty_cache()
+
+    out = {
+        "metric": "EC-MoE layer tokens/sec (1 GPU)", "value": head["value"], "unit": "tokens/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": head["ms_per_step"],
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": head["dtype"], "data": "synthetic", "config": head["config"],
+        "roofline": head["roofline"], "cpu_baseline": head.get("cpu_baseline"), "stages": head["stages"],
+    }
+    for key in ("step_tflops", "routing"):
+        if key in head:
+            out[key] = head[key]
+    if not single:
+        out["workloads"] = {}
+        for name in OTHERS:
+            out["workloads"][name] = run_workload(args, m, wl, torch, np, name, variants=False, cpu_baseline=False)
+            torch.cuda.empty_cache()
+        if not args.no_context:
+            out["context"] = vendor_context(torch, wl, (HEADLINE,) + OTHERS)
     print(json.dumps(out), flush=True)
     return 0
 

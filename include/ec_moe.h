@@ -234,6 +234,22 @@ int ec_moe_backward(const void* dY, const void* X, const void* Wg, const void* W
                     int64_t n, int64_t d, int64_t e, int64_t k, int64_t d_ff, int act, int dtype,
                     void* ws, size_t ws_bytes, void* stream);
 
+/* Measurement aid: ec_moe_backward with a HIP event recorded on `stream` before the first and after every
+ * stage of the pass; the call then WAITS for the last event (the only entry point that synchronises) and
+ * writes the stages' durations in milliseconds to stage_ms (HOST pointer, EC_MOE_BWD_STAGES floats).
+ * Stages, in order (ec_moe_backward_stage_name(i), NULL outside 0..EC_MOE_BWD_STAGES-1): dX_e and dG rows of
+ * Eq. 4; dW2 = H^T dX_e; dA = (dX_e W2^T) act'(A); dW1 = X_in^T dA; dX_in = dA W1^T; the token-major index;
+ * the softmax derivative dZ; the two gate products (dWg = X^T dZ, dZ Wg^T); the scatter-add into dX.
+ * Results and errors as ec_moe_backward.  Creates and destroys its events (host objects; no device memory). */
+#define EC_MOE_BWD_STAGES 9
+int ec_moe_backward_timed(const void* dY, const void* X, const void* Wg, const void* W1, const void* W2,
+                          const float* S, const float* G, const int32_t* I,
+                          const void* Xin, const void* A, const void* H, const void* Xe,
+                          void* dX, float* dWg, float* dW1, float* dW2,
+                          int64_t n, int64_t d, int64_t e, int64_t k, int64_t d_ff, int act, int dtype,
+                          void* ws, size_t ws_bytes, void* stream, float* stage_ms);
+const char* ec_moe_backward_stage_name(int stage);
+
 /* hipError_t (as int) of the calling thread's most recent EC_ERR_HIP, else 0. */
 int ec_moe_last_hip_error(void);
 

@@ -58,6 +58,8 @@ _SIGNATURES = {
     "ec_moe_forward_capped": (c_int, [_P, _P, _P, _P, c_double, c_double, c_double, _I64, _P, _P, _P, _P, _P, _P,
                                       _I64, _I64, _I64, _I64, c_int, c_int, _P, _SZ, _P]),
     "ec_moe_backward": (c_int, [_P] * 16 + [_I64] * 5 + [c_int, c_int, _P, _SZ, _P]),
+    "ec_moe_backward_timed": (c_int, [_P] * 16 + [_I64] * 5 + [c_int, c_int, _P, _SZ, _P, ctypes.POINTER(ctypes.c_float)]),
+    "ec_moe_backward_stage_name": (c_char_p, [c_int]),
     "ec_moe_last_hip_error": (c_int, []),
     "ec_moe_status_string": (c_char_p, [c_int]),
     "ec_moe_version": (c_char_p, []),
@@ -274,6 +276,25 @@ def ec_moe_backward(dY, X, Wg, W1, W2, S, G, I, Xin, A, H, Xe, dX, dWg, dW1, dW2
         _ptr(dY, dt), _ptr(X), _ptr(Wg, dt), _ptr(W1, dt), _ptr(W2, dt), _ptr(S, f32), _ptr(G, f32),
         _ptr(I, torch.int32), _ptr(Xin, dt), _ptr(A, dt), _ptr(H, dt), _ptr(Xe, dt), _ptr(dX, dt), _ptr(dWg, f32),
         _ptr(dW1, f32), _ptr(dW2, f32), n, d, e, k, d_ff, act, _dtype_code(X), wp, wb, _stream()))
+
+
+EC_MOE_BWD_STAGES = 9
+
+
+def ec_moe_backward_timed(dY, X, Wg, W1, W2, S, G, I, Xin, A, H, Xe, dX, dWg, dW1, dW2, act: int, ws) -> dict:
+    """ec_moe_backward with HIP events between its stages; waits, returns {stage name: milliseconds}."""
+    n, d = X.shape
+    e, k = I.shape
+    d_ff = W1.shape[2]
+    wp, wb = _ws(ws)
+    dt = X.dtype
+    f32 = torch.float32
+    ms = (ctypes.c_float * EC_MOE_BWD_STAGES)()
+    _check("ec_moe_backward_timed", lib().ec_moe_backward_timed(
+        _ptr(dY, dt), _ptr(X), _ptr(Wg, dt), _ptr(W1, dt), _ptr(W2, dt), _ptr(S, f32), _ptr(G, f32),
+        _ptr(I, torch.int32), _ptr(Xin, dt), _ptr(A, dt), _ptr(H, dt), _ptr(Xe, dt), _ptr(dX, dt), _ptr(dWg, f32),
+        _ptr(dW1, f32), _ptr(dW2, f32), n, d, e, k, d_ff, act, _dtype_code(X), wp, wb, _stream(), ms))
+    return {lib().ec_moe_backward_stage_name(i).decode(): float(ms[i]) for i in range(EC_MOE_BWD_STAGES)}
 
 
 def ec_moe_last_hip_error() -> int:

@@ -224,9 +224,16 @@ static int forward_impl(const void* X, const void* Wg, const void* W1, const voi
     }
     void* H = H_out ? H_out : at(ws, L.h);
     void* Xe = Xe_out ? Xe_out : at(ws, L.xe);
-    rc = launch_ffn(fused_gather ? nullptr : Xin, X, I, n, W1, W2, Xe, A_out, H, e, k, d, d_ff, act, dtype, st);
+    // Eq. 4's weight G[i,j] is applied in the second product's epilogue (fp32, before the row's one rounding) when
+    // nobody asks for X_e itself; the combine is then a plain expert-ordered sum of rows.
+#ifndef EC_MOE_SCALE_IN_EPILOGUE
+#define EC_MOE_SCALE_IN_EPILOGUE 0
+#endif
+    const bool scaled_rows = EC_MOE_SCALE_IN_EPILOGUE && Xe_out == nullptr && ffn_can_scale_rows(dtype, k, d, d_ff);
+    rc = launch_ffn(fused_gather ? nullptr : Xin, X, I, n, W1, W2, Xe, A_out, H, e, k, d, d_ff, act, dtype, st,
+                    scaled_rows ? G : nullptr);
     if (rc != EC_OK) return rc;
-    return launch_combine(Xe, G, I, Xout, n, d, e, k, dtype, ix, st);
+    return launch_combine(Xe, scaled_rows ? nullptr : G, I, Xout, n, d, e, k, dtype, ix, st);
 }
 
 int ec_moe_forward(const void* X, const void* Wg, const void* W1, const void* W2, double c, void* Xout,
@@ -391,6 +398,52 @@ int ec_moe_backward(const void* dY, const void* X, const void* Wg, const void* W
     if (!ws_ok(ws, ws_bytes, L.total)) return EC_ERR_WORKSPACE;
     return launch_backward(dY, X, Wg, W1, W2, S, G, I, Xin, A, H, Xe, dX, dWg, dW1, dW2, n, d, e, k, d_ff, act,
                            dtype, ws, L, (hipStream_t)stream);
+}
+
+int ec_moe_backward_timed(const void* dY, const void* X, const void* Wg, const void* W1, const void* W2, const float* S,
+                          const float* G, const int32_t* I, const void* Xin, const void* A, const void* H,
+                          const void* Xe, void* dX, float* dWg, float* dW1, float* dW2, int64_t n, int64_t d, int64_t e,
+                          int64_t k, int64_t d_ff, int act, int dtype, void* ws, size_t ws_bytes, void* stream,
+                          float* stage_ms) {
+    if (!stage_ms || !dY || !X || !Wg || !W1 || !W2 || !S || !G || !I || !Xin || !A || !H || !Xe || !dX || !dWg || !dW1 ||
+        !dW2 || !sizes_ok(n, d, e, k) || d_ff <= 0 || d_ff >= (int64_t)1 << 31 || !dtype_ok(dtype) ||
+        !act_ok(act) || !width_ok(d, dtype) || !width_ok(d_ff, dtype) ||
+        !all_aligned(dY, X, Wg, W1, W2, S, G, I, Xin, A, H, Xe, dX, dWg, dW1, dW2))
+        return EC_ERR_INVALID_ARG;
+    const WsLayout L = ws_layout(n, d, e, k, d_ff, dtype, 1);
+    if (!ws_ok(ws, ws_bytes, L.total)) return EC_ERR_WORKSPACE;
+    hipEvent_t marks[BWD_STAGES + 1];
+    int made = 0;
+    hipError_t err = hipSuccess;
+    for (; made <= BWD_STAGES && err == hipSuccess; ++made) err = hipEventCreate(&marks[made]);
+    int rc = EC_OK;
+    if (err != hipSuccess) {
+        --made;  // the last create failed
+        set_last_hip_error(err);
+        rc = EC_ERR_HIP;
+    } else {
+        rc = launch_backward(dY, X, Wg, W1, W2, S, G, I, Xin, A, H, Xe, dX, dWg, dW1, dW2, n, d, e, k, d_ff, act, dtype,
+                             ws, L, (hipStream_t)stream, marks);
+        if (rc == EC_OK) {
+            err = hipEventSynchronize(marks[BWD_STAGES]);
+            for (int s = 0; s < BWD_STAGES && err == hipSuccess; ++s)
+                err = hipEventElapsedTime(&stage_ms[s], marks[s], marks[s + 1]);
+            if (err != hipSuccess) {
+                set_last_hip_error(err);
+                rc = EC_ERR_HIP;
+            }
+        } else {
+            (void)hipStreamSynchronize((hipStream_t)stream);  // nothing may still refer to the events
+        }
+    }
+    for (int s = 0; s < made; ++s) (void)hipEventDestroy(marks[s]);
+    return rc;
+}
+
+const char* ec_moe_backward_stage_name(int stage) {
+    static const char* const names[BWD_STAGES] = {"bwd_rows", "bwd_dW2", "bwd_dA", "bwd_dW1", "bwd_dX_in",
+                                                  "bwd_index", "bwd_dZ", "bwd_gate_products", "bwd_scatter"};
+    return stage >= 0 && stage < BWD_STAGES ? names[stage] : nullptr;
 }
 
 int ec_moe_last_hip_error(void) { return g_last_hip_error; }

@@ -2,7 +2,7 @@
 // selection I held constant and the gate values G = S[I[i,j], i] differentiable (Sec. 3.4: the gating
 // network is trained through the top-k function).  With r = (i,j) a bucket row and l = I[i,j]:
 //   dX_e[r,:] = G[r] dY[l,:]                 dG[r]  = <dY[l,:], X_e[r,:]>               (Eq. 4)
-//   dW2[i] = H[i]^T dX_e[i]                  dH[i]  = dX_e[i] W2[i]^T
+//   dW2[i] = H[i]^T dX_e[i]                  dH[r,:] = dX_e[r,:] W2[i]^T = G[r] (dY[l,:] W2[i]^T)
 //   dA = dH * act'(A)                        dW1[i] = X_in[i]^T dA[i]    dX_in[i] = dA[i] W1[i]^T   (Eq. 3)
 //   dS[l,i] = dG[r] on selected pairs, else 0;  dZ[l,:] = S[l,:] * (dS[l,:] - <dS[l,:], S[l,:]>)   (softmax)
 //   dWg = X^T dZ                             dX[l,:] = dZ[l,:] Wg^T + sum_{r: I[r]=l} dX_in[r,:]   (Eq. 2, 3)
@@ -17,28 +17,29 @@ namespace ecmoe {
 // ---------------------------------------------------------------------------
 // dX_e and dG: one wavefront per bucket row.
 // ---------------------------------------------------------------------------
-template <typename T, int VEC>
+template <typename T, int VEC, typename TOut>
 __global__ void __launch_bounds__(256)
 bwd_rows_kernel(const T* __restrict__ dY, const T* __restrict__ Xe, const float* __restrict__ G,
-                const int32_t* __restrict__ I, T* __restrict__ dXe, float* __restrict__ dG, long long rows, int d) {
+                const int32_t* __restrict__ I, TOut* __restrict__ dXe, float* __restrict__ dG, long long rows, int d) {
     typedef T vec_t __attribute__((ext_vector_type(VEC)));  // VEC elements = 16 bytes when the rows allow it
+    typedef TOut ovec_t __attribute__((ext_vector_type(VEC)));
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int nvec = d / VEC;
     for (long long r = (long long)blockIdx.x * 4 + wave; r < rows; r += (long long)gridDim.x * 4) {
         const int tok = I[r];  // -1: an empty buffer row (token-choice routing) fed nothing: zero gradient
         const vec_t* src = reinterpret_cast<const vec_t*>(dY + (size_t)(tok < 0 ? 0 : tok) * d);
         const vec_t* xe = reinterpret_cast<const vec_t*>(Xe + (size_t)r * d);
-        vec_t* dst = reinterpret_cast<vec_t*>(dXe + (size_t)r * d);
+        ovec_t* dst = reinterpret_cast<ovec_t*>(dXe + (size_t)r * d);
         const float g = tok < 0 ? 0.0f : G[r];
         float dot = 0.0f;
         for (int t = lane; t < nvec; t += kWave) {
             const vec_t y = src[t], x = xe[t];
-            vec_t o;
+            ovec_t o;
 #pragma unroll
             for (int q = 0; q < VEC; ++q) {
                 const float yf = Cvt<T>::to_f32(y[q]);
                 dot = fmaf(yf, Cvt<T>::to_f32(x[q]), dot);
-                o[q] = Cvt<T>::from_f32(g * yf);
+                o[q] = Cvt<TOut>::from_f32(g * yf);
             }
             dst[t] = o;
         }
@@ -94,17 +95,17 @@ bwd_dz_kernel(const float* __restrict__ S, const float* __restrict__ dG, const i
 //   TRA: A[g] stored [K][M] instead of [M][K];  TRB: B[g] stored [N][K] instead of [K][N].
 //   MULGRAD: C = acc * act'(aux[m][n]).
 // ---------------------------------------------------------------------------
-template <typename TA, typename TB, typename TC, bool TRA, bool TRB, bool MULGRAD, int ACT>
+template <typename TA, typename TB, typename TC, bool TRA, bool TRB, bool MULGRAD, int ACT, typename TAux = TC>
 __global__ void __launch_bounds__(256)
 gemm_plain_kernel(const TA* __restrict__ Ag, const TB* __restrict__ Bg, TC* __restrict__ Cg,
-                  const TC* __restrict__ auxg, int M, int N, int K, long long sA, long long sB, long long sC) {
+                  const TAux* __restrict__ auxg, int M, int N, int K, long long sA, long long sB, long long sC) {
     __shared__ float As[16][64 + 4];  // [k][m]
     __shared__ float Bs[16][64 + 4];  // [k][n]
     const int g = blockIdx.z;
     const TA* A = Ag + (size_t)g * sA;
     const TB* B = Bg + (size_t)g * sB;
     TC* C = Cg + (size_t)g * sC;
-    const TC* aux = MULGRAD ? auxg + (size_t)g * sC : nullptr;
+    const TAux* aux = MULGRAD ? auxg + (size_t)g * sC : nullptr;
     const int m0 = blockIdx.y * 64, n0 = blockIdx.x * 64;
     const int tid = threadIdx.x, tx = tid & 15, ty = tid >> 4;
     float acc[4][4] = {};
@@ -146,7 +147,7 @@ gemm_plain_kernel(const TA* __restrict__ Ag, const TB* __restrict__ Bg, TC* __re
             if (gm < M && gn < N) {
                 float v = acc[i][j];
                 if (MULGRAD) {
-                    const float a = Cvt<TC>::to_f32(aux[(size_t)gm * N + gn]);
+                    const float a = Cvt<TAux>::to_f32(aux[(size_t)gm * N + gn]);
                     float gr = 1.0f;
                     if (ACT == EC_ACT_RELU) gr = a > 0.0f ? 1.0f : 0.0f;
                     if (ACT == EC_ACT_GELU) {
@@ -160,27 +161,34 @@ gemm_plain_kernel(const TA* __restrict__ Ag, const TB* __restrict__ Bg, TC* __re
         }
 }
 
+// grid.y carries the row tiles and grid.z the groups: both are limited to 65535
+static bool plain_grid_ok(int G, int M) { return (M + 63) / 64 <= 65535 && G <= 65535; }
+
 template <typename TA, typename TB, typename TC, bool TRA, bool TRB>
-static void gemm_plain(const TA* A, const TB* B, TC* C, int G, int M, int N, int K, long long sA, long long sB,
-                       long long sC, hipStream_t stream) {
+static int gemm_plain(const TA* A, const TB* B, TC* C, int G, int M, int N, int K, long long sA, long long sB,
+                      long long sC, hipStream_t stream) {
+    if (!plain_grid_ok(G, M)) return EC_ERR_UNSUPPORTED;
     dim3 grid((unsigned)((N + 63) / 64), (unsigned)((M + 63) / 64), (unsigned)G);
     hipLaunchKernelGGL((gemm_plain_kernel<TA, TB, TC, TRA, TRB, false, EC_ACT_IDENTITY>), grid, dim3(256), 0, stream, A, B,
                        C, (const TC*)nullptr, M, N, K, sA, sB, sC);
+    return EC_OK;
 }
 template <typename T>
-static void gemm_plain_mulgrad(const T* A, const T* B, T* C, const T* aux, int G, int M, int N, int K, int act,
-                               hipStream_t stream) {  // A [M][K], B stored [N][K]
+static int gemm_plain_mulgrad(const float* A, const T* B, float* C, const T* aux, int G, int M, int N, int K, int act,
+                              hipStream_t stream) {  // A [M][K] fp32, B stored [N][K]
+    if (!plain_grid_ok(G, M)) return EC_ERR_UNSUPPORTED;
     dim3 grid((unsigned)((N + 63) / 64), (unsigned)((M + 63) / 64), (unsigned)G);
     const long long sA = (long long)M * K, sB = (long long)N * K, sC = (long long)M * N;
     if (act == EC_ACT_RELU)
-        hipLaunchKernelGGL((gemm_plain_kernel<T, T, T, false, true, true, EC_ACT_RELU>), grid, dim3(256), 0, stream, A, B, C,
-                           aux, M, N, K, sA, sB, sC);
+        hipLaunchKernelGGL((gemm_plain_kernel<float, T, float, false, true, true, EC_ACT_RELU, T>), grid, dim3(256), 0,
+                           stream, A, B, C, aux, M, N, K, sA, sB, sC);
     else if (act == EC_ACT_GELU)
-        hipLaunchKernelGGL((gemm_plain_kernel<T, T, T, false, true, true, EC_ACT_GELU>), grid, dim3(256), 0, stream, A, B, C,
-                           aux, M, N, K, sA, sB, sC);
+        hipLaunchKernelGGL((gemm_plain_kernel<float, T, float, false, true, true, EC_ACT_GELU, T>), grid, dim3(256), 0,
+                           stream, A, B, C, aux, M, N, K, sA, sB, sC);
     else
-        hipLaunchKernelGGL((gemm_plain_kernel<T, T, T, false, true, true, EC_ACT_IDENTITY>), grid, dim3(256), 0, stream, A,
-                           B, C, aux, M, N, K, sA, sB, sC);
+        hipLaunchKernelGGL((gemm_plain_kernel<float, T, float, false, true, true, EC_ACT_IDENTITY, T>), grid, dim3(256), 0,
+                           stream, A, B, C, aux, M, N, K, sA, sB, sC);
+    return EC_OK;
 }
 
 // Sum of `splits` partial [rows] vectors in split order.
@@ -225,22 +233,30 @@ duplicate_columns_kernel(const bf16_t* __restrict__ Wg, bf16_t* __restrict__ Wg2
 // Workspace of the backward pass (after the forward layout, at L.bwd).
 // ---------------------------------------------------------------------------
 struct BwdLayout {
-    size_t dxe, dg, da, dxin, dz, dzb, dxz, wg_part, wg2, total;
+    size_t dxe, dg, da, da_lo, dxin, dz, dzb, dxz, wg_part, wg2, total;
     int splits;
     int64_t split_len;
+    bool mfma;  // the four expert products run on the matrix cores
 };
 
 static BwdLayout bwd_layout(int64_t n, int64_t d, int64_t e, int64_t k, int64_t d_ff, int dtype) {
     BwdLayout B;
-    const size_t es = elem_size(dtype);
     size_t off = 0;
     auto take = [&](size_t bytes) { size_t a = off; off = align_up(off + bytes, 256); return a; };
     B.split_len = 512;  // tokens per partial sum of dWg
     B.splits = (int)ceil_div(n, B.split_len);
-    B.dxe = take((size_t)e * k * d * es);
+    // matrix-core path: bf16, contraction-contiguous operands need d, d_ff % 64 == 0, the rows of dY are gathered
+    // through one buffer descriptor
+    B.mfma = dtype == EC_BF16 && gemm_bf16_shape_ok(k, d_ff, d) && gemm_bf16_shape_ok(k, d, d_ff) &&
+             gemm_bf16_shape_ok(d_ff, d, k, false, true) && gemm_bf16_shape_ok(d, d_ff, k, false, true) &&
+             n * d * 2 < ((int64_t)1 << 31) - 65536;
+    // Intermediates: bf16 where they are matrix-core operands (dA as high part + remainder), fp32 on the plain path.
+    const size_t is = B.mfma ? 2 : 4;
+    B.dxe = take((size_t)e * k * d * is);
     B.dg = take((size_t)e * k * 4);
-    B.da = take((size_t)e * k * d_ff * es);
-    B.dxin = take((size_t)e * k * d * 4);  // fp32 on the matrix-core path (kept unrounded), else `es` bytes per element
+    B.da = take((size_t)e * k * d_ff * is);
+    B.da_lo = take(B.mfma ? (size_t)e * k * d_ff * 2 : 0);
+    B.dxin = take((size_t)e * k * d * 4);  // fp32 on both paths: it is only summed into dX
     B.dz = take((size_t)n * e * 4);
     B.dzb = take((size_t)n * e * 2 * 2);                   // [n][hi | lo]
     B.dxz = take((size_t)n * d * 4);
@@ -258,13 +274,18 @@ template <typename T>
 static int backward_typed(const T* dY, const T* X, const T* Wg, const T* W1, const T* W2, const float* S, const float* G,
                           const int32_t* I, const T* Xin, const T* A, const T* H, const T* Xe, T* dX, float* dWg,
                           float* dW1, float* dW2, int64_t n, int64_t d, int64_t e, int64_t k, int64_t d_ff, int act,
-                          int dtype, void* ws, const WsLayout& L, hipStream_t stream) {
+                          int dtype, void* ws, const WsLayout& L, hipStream_t stream, hipEvent_t* marks) {
+    // marks (optional, BWD_STAGES + 1 events): recorded on the stream before the first stage and after every stage
+    int mark_at = 0;
+    auto mark = [&]() {
+        if (marks != nullptr) (void)hipEventRecord(marks[mark_at], stream);
+        ++mark_at;
+    };
+    mark();
     unsigned char* base = static_cast<unsigned char*>(ws) + L.bwd;
     const BwdLayout B = bwd_layout(n, d, e, k, d_ff, dtype);
-    T* dXe = reinterpret_cast<T*>(base + B.dxe);
     float* dG = reinterpret_cast<float*>(base + B.dg);
-    T* dA = reinterpret_cast<T*>(base + B.da);
-    T* dXin = reinterpret_cast<T*>(base + B.dxin);
+    float* dXin = reinterpret_cast<float*>(base + B.dxin);
     float* dZ = reinterpret_cast<float*>(base + B.dz);
     bf16_t* dZb = reinterpret_cast<bf16_t*>(base + B.dzb);
     float* dXz = reinterpret_cast<float*>(base + B.dxz);
@@ -272,9 +293,7 @@ static int backward_typed(const T* dY, const T* X, const T* Wg, const T* W1, con
     const long long rows = (long long)e * k;
     const int Gn = (int)e, Mk = (int)k, D = (int)d, F = (int)d_ff;
     constexpr bool BF = sizeof(T) == 2;
-    // matrix-core path for the four expert products: bf16, contraction-contiguous operands need d, d_ff % 64 == 0
-    const bool mfma = BF && gemm_bf16_shape_ok(k, d_ff, d) && gemm_bf16_shape_ok(k, d, d_ff) &&
-                      gemm_bf16_shape_ok(d_ff, d, k, false, true) && gemm_bf16_shape_ok(d, d_ff, k, false, true);
+    const bool mfma = BF && B.mfma;
 
     // Matrix-core path for the two gate products (dWg = X^T dZ, dZ Wg^T): whole splits of 512 tokens, experts
     // a multiple of 32 (the contraction of the second product is 2e), 16-byte rows.  dZ enters as hi + lo,
@@ -284,48 +303,81 @@ static int backward_typed(const T* dY, const T* X, const T* Wg, const T* W1, con
                            gemm_bf16_shape_ok(d, 2 * e, B.split_len, false, true) && gemm_bf16_shape_ok(n, d, 2 * e);
     bf16_t* Wg2 = reinterpret_cast<bf16_t*>(base + B.wg2);
 
-    // Eq. 4 backwards: dX_e, dG
+    // Eq. 4 backwards: dX_e, dG (dX_e in bf16 as a matrix-core operand, in fp32 on the plain path)
     {
         long long blocks = ceil_div(rows, 4);
         if (blocks > (1 << 20)) blocks = 1 << 20;
         constexpr int V16 = 16 / (int)sizeof(T);
-        if (d % V16 == 0)
-            hipLaunchKernelGGL((bwd_rows_kernel<T, V16>), dim3((unsigned)blocks), dim3(256), 0, stream, dY, Xe, G, I, dXe, dG,
-                               rows, D);
-        else
-            hipLaunchKernelGGL((bwd_rows_kernel<T, 1>), dim3((unsigned)blocks), dim3(256), 0, stream, dY, Xe, G, I, dXe, dG,
-                               rows, D);
+        const dim3 grid((unsigned)blocks), block(256);
+        void* dXe = base + B.dxe;
+        if (mfma) {
+            if (d % V16 == 0)
+                hipLaunchKernelGGL((bwd_rows_kernel<T, V16, T>), grid, block, 0, stream, dY, Xe, G, I, (T*)dXe, dG, rows, D);
+            else
+                hipLaunchKernelGGL((bwd_rows_kernel<T, 1, T>), grid, block, 0, stream, dY, Xe, G, I, (T*)dXe, dG, rows, D);
+        } else {
+            if (d % V16 == 0)
+                hipLaunchKernelGGL((bwd_rows_kernel<T, V16, float>), grid, block, 0, stream, dY, Xe, G, I, (float*)dXe, dG,
+                                   rows, D);
+            else
+                hipLaunchKernelGGL((bwd_rows_kernel<T, 1, float>), grid, block, 0, stream, dY, Xe, G, I, (float*)dXe, dG,
+                                   rows, D);
+        }
     }
+    mark();  // 0: rows
     // Eq. 3 backwards
     if (mfma) {
         if constexpr (BF) {
-            const bf16_t *bdXe = (const bf16_t*)dXe, *bH = (const bf16_t*)H, *bXin = (const bf16_t*)Xin;
+            const bf16_t *bdXe = reinterpret_cast<const bf16_t*>(base + B.dxe), *bH = (const bf16_t*)H,
+                         *bXin = (const bf16_t*)Xin;
+            bf16_t* dA = reinterpret_cast<bf16_t*>(base + B.da);       // high part: bf16(dA)
+            bf16_t* dAlo = reinterpret_cast<bf16_t*>(base + B.da_lo);  // remainder: bf16(dA - high part)
             // dW2[i] = H[i]^T dX_e[i]     (A stored [k][d_ff], B [k][d]) -> fp32 [d_ff][d]
             gemm_bf16_launch<256, 256, 2, 1, true, false, EPI_F32, EC_ACT_IDENTITY>(bH, bdXe, dW2, nullptr, Gn, F, D, Mk,
                                                                                     nullptr, 0, stream);
-            // dA[i] = (dX_e[i] W2[i]^T) * act'(A[i])   (B = W2 stored [d_ff][d] = [N][K])
+            mark();  // 1: dW2
+            // dA[i] = (dX_e[i] W2[i]^T) * act'(A[i]) with dX_e[r,:] = G[r] dY[I[r],:]: the rows of dY are gathered by
+            // the tile loader (exact bf16 operands) and G[r] multiplies the fp32 result in the epilogue, so dA -- and
+            // through it dX -- does not inherit the bf16 rounding of dX_e   (B = W2 stored [d_ff][d] = [N][K]).
+            // The epilogue also keeps what the bf16 rounding of dA drops (dAlo), for the product that feeds dX.
 #define EC_BWD_DA(ACTV)                                                                                              \
-    gemm_bf16_launch<256, 256, 2, 1, false, true, EPI_MULGRAD, ACTV>(bdXe, (const bf16_t*)W2, dA, (void*)A, Gn, Mk, F, D, \
-                                                                     nullptr, 0, stream)
+    gemm_bf16_launch<256, 256, 2, 1, false, true, EPI_MULGRAD, ACTV>((const bf16_t*)dY, (const bf16_t*)W2, dA, (void*)A, \
+                                                                     Gn, Mk, F, D, I, (int)n, stream, G, nullptr, dAlo)
             if (act == EC_ACT_RELU) EC_BWD_DA(EC_ACT_RELU);
             else if (act == EC_ACT_GELU) EC_BWD_DA(EC_ACT_GELU);
             else EC_BWD_DA(EC_ACT_IDENTITY);
 #undef EC_BWD_DA
+            mark();  // 2: dA
             // dW1[i] = X_in[i]^T dA[i]    -> fp32 [d][d_ff]
             gemm_bf16_launch<256, 256, 2, 1, true, false, EPI_F32, EC_ACT_IDENTITY>(bXin, (const bf16_t*)dA, dW1, nullptr, Gn,
                                                                                     D, F, Mk, nullptr, 0, stream);
-            // dX_in[i] = dA[i] W1[i]^T    (B = W1 stored [d][d_ff] = [N][K]); kept in fp32: it is only summed into dX
-            gemm_bf16_launch<256, 256, 2, 1, false, true, EPI_F32, EC_ACT_IDENTITY>((const bf16_t*)dA, (const bf16_t*)W1, dXin,
-                                                                                    nullptr, Gn, Mk, D, F, nullptr, 0, stream);
+            mark();  // 3: dW1
+            // dX_in[i] = (dA[i] + dAlo[i]) W1[i]^T    (B = W1 stored [d][d_ff] = [N][K]); kept in fp32: it is only
+            // summed into dX.  A token's gradient row scales with its gate value while the error bar is relative to
+            // the whole tensor, so a single bf16 rounding of dA (2^-9) is what decides the worst element of dX;
+            // with the remainder the product sees dA to 2^-17, at twice the work of this one product.
+            gemm_bf16_launch<256, 256, 2, 1, false, true, EPI_F32, EC_ACT_IDENTITY, true>(
+                (const bf16_t*)dA, (const bf16_t*)W1, dXin, nullptr, Gn, Mk, D, F, nullptr, 0, stream, nullptr, dAlo, nullptr);
+            mark();  // 4: dX_in
         }
     } else {
-        gemm_plain<T, T, float, true, false>(H, dXe, dW2, Gn, F, D, Mk, (long long)k * d_ff, (long long)k * d,
-                                             (long long)d_ff * d, stream);
-        gemm_plain_mulgrad<T>(dXe, W2, dA, A, Gn, Mk, F, D, act, stream);
-        gemm_plain<T, T, float, true, false>(Xin, dA, dW1, Gn, D, F, Mk, (long long)k * d, (long long)k * d_ff,
-                                             (long long)d * d_ff, stream);
-        gemm_plain<T, T, T, false, true>(dA, W1, dXin, Gn, Mk, D, F, (long long)k * d_ff, (long long)d * d_ff,
-                                         (long long)k * d, stream);
+        // plain path: every intermediate (dX_e, dA, dX_in) stays in fp32
+        const float* dXe = reinterpret_cast<const float*>(base + B.dxe);
+        float* dA = reinterpret_cast<float*>(base + B.da);
+        int prc = gemm_plain<T, float, float, true, false>(H, dXe, dW2, Gn, F, D, Mk, (long long)k * d_ff, (long long)k * d,
+                                                           (long long)d_ff * d, stream);
+        mark();
+        if (prc == EC_OK) prc = gemm_plain_mulgrad<T>(dXe, W2, dA, A, Gn, Mk, F, D, act, stream);
+        mark();
+        if (prc == EC_OK)
+            prc = gemm_plain<T, float, float, true, false>(Xin, dA, dW1, Gn, D, F, Mk, (long long)k * d,
+                                                           (long long)k * d_ff, (long long)d * d_ff, stream);
+        mark();
+        if (prc == EC_OK)
+            prc = gemm_plain<float, T, float, false, true>(dA, W1, dXin, Gn, Mk, D, F, (long long)k * d_ff,
+                                                           (long long)d * d_ff, (long long)k * d, stream);
+        mark();
+        if (prc != EC_OK) return prc;
     }
     int rc = check_launch();
     if (rc != EC_OK) return rc;
@@ -337,6 +389,7 @@ static int backward_typed(const T* dY, const T* X, const T* Wg, const T* W1, con
     if (rc != EC_OK) return rc;
     rc = launch_combine_csr(I, n, e, k, ix, stream);
     if (rc != EC_OK) return rc;
+    mark();  // 5: token-major index
 
     // Eq. 2 backwards: dZ, then dWg = X^T dZ (fixed-order split sums) and the dense part of dX
     {
@@ -345,6 +398,7 @@ static int backward_typed(const T* dY, const T* X, const T* Wg, const T* W1, con
         hipLaunchKernelGGL(bwd_dz_kernel, dim3((unsigned)blocks), dim3(256), 0, stream, S, dG, ix.offsets, ix.inv, dZ,
                            mfma_gate ? dZb : (bf16_t*)nullptr, (int)n, (int)e, (int)k);
     }
+    mark();  // 6: dZ
     if (mfma_gate) {
         if constexpr (BF) {
             // partial[s] = X[s*512 ..]^T [hi | lo][s*512 ..]: one group per split, both operands row-indexed
@@ -363,40 +417,48 @@ static int backward_typed(const T* dY, const T* X, const T* Wg, const T* W1, con
     } else {
     {   // partial[s] = X[s*len .. ]^T dZ[s*len .. ]   (the last split is shorter; its K is passed per launch)
         const int full = (int)(n / B.split_len);
+        int prc = EC_OK;
         if (full > 0)
-            gemm_plain<T, float, float, true, false>(X, dZ, wg_part, full, D, (int)e, (int)B.split_len,
-                                                     (long long)B.split_len * d, (long long)B.split_len * e,
-                                                     (long long)d * e, stream);
+            prc = gemm_plain<T, float, float, true, false>(X, dZ, wg_part, full, D, (int)e, (int)B.split_len,
+                                                           (long long)B.split_len * d, (long long)B.split_len * e,
+                                                           (long long)d * e, stream);
         const int64_t rest = n - (int64_t)full * B.split_len;
-        if (rest > 0)
-            gemm_plain<T, float, float, true, false>(X + (size_t)full * B.split_len * d, dZ + (size_t)full * B.split_len * e,
-                                                     wg_part + (size_t)full * d * e, 1, D, (int)e, (int)rest, 0, 0, 0,
-                                                     stream);
+        if (prc == EC_OK && rest > 0)
+            prc = gemm_plain<T, float, float, true, false>(X + (size_t)full * B.split_len * d,
+                                                           dZ + (size_t)full * B.split_len * e,
+                                                           wg_part + (size_t)full * d * e, 1, D, (int)e, (int)rest, 0, 0,
+                                                           0, stream);
+        if (prc != EC_OK) return prc;
         long long cnt = (long long)d * e, blocks = (cnt + 255) / 256;
         hipLaunchKernelGGL(reduce_splits_kernel, dim3((unsigned)(blocks > 4096 ? 4096 : blocks)), dim3(256), 0, stream,
                            wg_part, dWg, cnt, B.splits);
     }
     // dXz = dZ Wg^T  (Wg stored [d][e] = [N][K])
-    gemm_plain<float, T, float, false, true>(dZ, Wg, dXz, 1, (int)n, D, (int)e, 0, 0, 0, stream);
+    const int prc = gemm_plain<float, T, float, false, true>(dZ, Wg, dXz, 1, (int)n, D, (int)e, 0, 0, 0, stream);
+    if (prc != EC_OK) return prc;
     }
     rc = check_launch();
     if (rc != EC_OK) return rc;
+    mark();  // 7: gate products (dWg, dZ Wg^T)
     // dX = dXz + scatter-add of dX_in rows, expert-ascending, rounded once
-    return launch_combine(dXin, nullptr, I, dX, n, d, e, k, dtype, ix, stream, dXz, true, nullptr, BF && mfma);
+    rc = launch_combine(dXin, nullptr, I, dX, n, d, e, k, dtype, ix, stream, dXz, true, nullptr, BF);
+    mark();  // 8: scatter into dX
+    return rc;
 }
 
 int launch_backward(const void* dY, const void* X, const void* Wg, const void* W1, const void* W2, const float* S,
                     const float* G, const int32_t* I, const void* Xin, const void* A, const void* H, const void* Xe,
                     void* dX, float* dWg, float* dW1, float* dW2, int64_t n, int64_t d, int64_t e, int64_t k,
-                    int64_t d_ff, int act, int dtype, void* ws, const WsLayout& L, hipStream_t stream) {
+                    int64_t d_ff, int act, int dtype, void* ws, const WsLayout& L, hipStream_t stream,
+                    hipEvent_t* marks) {
     if (dtype == EC_BF16)
         return backward_typed<bf16_t>((const bf16_t*)dY, (const bf16_t*)X, (const bf16_t*)Wg, (const bf16_t*)W1,
                                       (const bf16_t*)W2, S, G, I, (const bf16_t*)Xin, (const bf16_t*)A, (const bf16_t*)H,
                                       (const bf16_t*)Xe, (bf16_t*)dX, dWg, dW1, dW2, n, d, e, k, d_ff, act, dtype, ws, L,
-                                      stream);
+                                      stream, marks);
     return backward_typed<float>((const float*)dY, (const float*)X, (const float*)Wg, (const float*)W1, (const float*)W2,
                                  S, G, I, (const float*)Xin, (const float*)A, (const float*)H, (const float*)Xe, (float*)dX,
-                                 dWg, dW1, dW2, n, d, e, k, d_ff, act, dtype, ws, L, stream);
+                                 dWg, dW1, dW2, n, d, e, k, d_ff, act, dtype, ws, L, stream, marks);
 }
 
 }  // namespace ecmoe

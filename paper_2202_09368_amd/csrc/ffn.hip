@@ -3,13 +3,14 @@
 // Two grouped (one launch covers all experts) GEMMs: A = X_in.W1 with the
 // activation fused into the epilogue, then X_e = H.W2.
 //  * bf16: matrix cores (v_mfma_f32_32x32x16_bf16), fp32 accumulation, LDS-staged
-//    tiles.  Both products are "row-major x row-major": the left operand is
-//    contraction-contiguous, the right operand (the weights) is not, so its
-//    tile is transposed in registers on the way into LDS and both MFMA operands
-//    are then read as 16-byte contraction-contiguous vectors.
+//    tiles (gemm_bf16.h).  Both products are "row-major x row-major": the left
+//    operand is contraction-contiguous and read from LDS as 16-byte fragments;
+//    the right operand (the weights) keeps its own [k][columns] form in LDS and
+//    its fragments come from transposing LDS reads.  Widths that are not
+//    multiples of 64 take a predicated kernel that transposes the weight tile
+//    in registers instead.
 //  * fp32: plain FMA tiles (small parity configuration only).
 #include <cmath>
-#include <cstdlib>
 
 #include "ec_common.h"
 #include "gemm_bf16.h"
@@ -205,22 +206,32 @@ gemm_bf16_generic_kernel(GemmArgs p) {
     }
 }
 
+// True when the matrix-core kernel covers the product (with rows gathered from a [gather_rows, K] matrix if asked).
+static bool gemm_bf16_fast_ok(int64_t M, int64_t N, int64_t K, bool gather, int64_t gather_rows) {
+    return gemm_bf16_shape_ok(M, N, K) && (!gather || gather_rows * K * 2 < ((int64_t)1 << 31) - 65536);
+}
+
 template <int BM, int BN, int STAGES, int OCC>
-static void launch_gemm_bf16(const bf16_t* A, const bf16_t* B, bf16_t* C, bf16_t* Cpre, int G, int M, int N, int K,
-                             int act, const int32_t* gather, int gather_rows, hipStream_t stream) {
-    if (gemm_bf16_shape_ok(M, N, K) && (gather == nullptr || (int64_t)gather_rows * K * 2 < ((int64_t)1 << 31))) {
+static int launch_gemm_bf16(const bf16_t* A, const bf16_t* B, bf16_t* C, bf16_t* Cpre, int G, int M, int N, int K,
+                            int act, const int32_t* gather, int gather_rows, const float* row_scale,
+                            hipStream_t stream) {
+    if (gemm_bf16_fast_ok(M, N, K, gather != nullptr, gather_rows)) {
 #define EC_GEMM_CASE(ACTV)                                                                                       \
     if (Cpre) gemm_bf16_launch<BM, BN, STAGES, OCC, false, false, EPI_ACT_SAVE, ACTV>(A, B, C, Cpre, G, M, N, K,  \
                                                                                      gather, gather_rows, stream); \
     else gemm_bf16_launch<BM, BN, STAGES, OCC, false, false, EPI_ACT, ACTV>(A, B, C, nullptr, G, M, N, K, gather,  \
-                                                                           gather_rows, stream)
+                                                                           gather_rows, stream, row_scale)
         if (act == EC_ACT_RELU) { EC_GEMM_CASE(EC_ACT_RELU); }
         else if (act == EC_ACT_GELU) { EC_GEMM_CASE(EC_ACT_GELU); }
         else { EC_GEMM_CASE(EC_ACT_IDENTITY); }
 #undef EC_GEMM_CASE
-        return;
+        return check_launch();
     }
-    // general shapes: predicated kernel, 128 x 128 tiles (no gather support: callers materialise X_in)
+    // general shapes: predicated kernel, 128 x 128 tiles.  It reads its left operand as stored and knows no row
+    // weights: a caller that asked for either gets an error instead of a wrong product.
+    if (gather != nullptr || row_scale != nullptr) return EC_ERR_UNSUPPORTED;
+    if ((int64_t)M * K >= ((int64_t)1 << 31) || (int64_t)K * N >= ((int64_t)1 << 31) || (int64_t)M * N >= ((int64_t)1 << 31))
+        return EC_ERR_UNSUPPORTED;
     constexpr int GBM = 128, GBN = 128;
     GemmArgs p;
     p.A = A; p.B = B; p.C = C; p.Cpre = Cpre;
@@ -234,20 +245,22 @@ static void launch_gemm_bf16(const bf16_t* A, const bf16_t* B, bf16_t* C, bf16_t
         auto k1 = gemm_bf16_generic_kernel<GBM, GBN, ACTV, true>;                                                \
         auto k0 = gemm_bf16_generic_kernel<GBM, GBN, ACTV, false>;                                               \
         auto kern = Cpre ? k1 : k0;                                                                              \
-        (void)hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, \
-                                  (int)lds);                                                                     \
+        static std::atomic<bool> allowed[2][64];                                                                 \
+        gemm_allow_lds(reinterpret_cast<const void*>(kern), lds, allowed[Cpre ? 1 : 0]);                         \
         hipLaunchKernelGGL(kern, grid, block, lds, stream, p);                                                   \
     } while (0)
     if (act == EC_ACT_RELU) { EC_GEMM_CASE(EC_ACT_RELU); }
     else if (act == EC_ACT_GELU) { EC_GEMM_CASE(EC_ACT_GELU); }
     else { EC_GEMM_CASE(EC_ACT_IDENTITY); }
 #undef EC_GEMM_CASE
+    return check_launch();
 }
 
 // Tile configuration of a grouped product: the candidate with the lowest estimated time, taken as
 // (rounds of 256 compute units) x (tile area) / (relative rate of that configuration).
-static void gemm_bf16_dispatch(const bf16_t* A, const bf16_t* B, bf16_t* C, bf16_t* Cpre, int G, int M, int N,
-                               int K, int act, const int32_t* gather, int gather_rows, hipStream_t stream) {
+static int gemm_bf16_dispatch(const bf16_t* A, const bf16_t* B, bf16_t* C, bf16_t* Cpre, int G, int M, int N,
+                              int K, int act, const int32_t* gather, int gather_rows, const float* row_scale,
+                              hipStream_t stream) {
     auto cost = [&](int bm, int bn, int occ, double rate) {
         double tiles = (double)G * ((M + bm - 1) / bm) * ((N + bn - 1) / bn);
         double rounds = std::ceil(tiles / (256.0 * occ)) * occ;
@@ -263,17 +276,12 @@ static void gemm_bf16_dispatch(const bf16_t* A, const bf16_t* B, bf16_t* C, bf16
     // still shorter contractions: 128 x 128 tiles, twice as many workgroups in flight (measured on
     // K = 768: 98-102 us against 104-110 us for the 256 x 128 pairs)
     if (pick == 3 && K <= 768 && cost(128, 128, 2, 1.0) <= 1.25 * c0) pick = 2;
-    static const int forced = [] {  // tuning knob: EC_MOE_GEMM_TILE=0..4 forces one configuration
-        const char* v = std::getenv("EC_MOE_GEMM_TILE");
-        return v ? std::atoi(v) : -1;
-    }();
-    if (forced >= 0 && forced <= 4) pick = forced;
     switch (pick) {
-        case 0: launch_gemm_bf16<256, 256, 2, 1>(A, B, C, Cpre, G, M, N, K, act, gather, gather_rows, stream); break;
-        case 1: launch_gemm_bf16<256, 128, 2, 1>(A, B, C, Cpre, G, M, N, K, act, gather, gather_rows, stream); break;
-        case 2: launch_gemm_bf16<128, 128, 1, 2>(A, B, C, Cpre, G, M, N, K, act, gather, gather_rows, stream); break;
-        case 4: launch_gemm_bf16<256, 192, 2, 1>(A, B, C, Cpre, G, M, N, K, act, gather, gather_rows, stream); break;
-        default: launch_gemm_bf16<256, 128, 1, 2>(A, B, C, Cpre, G, M, N, K, act, gather, gather_rows, stream); break;
+        case 0: return launch_gemm_bf16<256, 256, 2, 1>(A, B, C, Cpre, G, M, N, K, act, gather, gather_rows, row_scale, stream);
+        case 1: return launch_gemm_bf16<256, 128, 2, 1>(A, B, C, Cpre, G, M, N, K, act, gather, gather_rows, row_scale, stream);
+        case 2: return launch_gemm_bf16<128, 128, 1, 2>(A, B, C, Cpre, G, M, N, K, act, gather, gather_rows, row_scale, stream);
+        case 4: return launch_gemm_bf16<256, 192, 2, 1>(A, B, C, Cpre, G, M, N, K, act, gather, gather_rows, row_scale, stream);
+        default: return launch_gemm_bf16<256, 128, 1, 2>(A, B, C, Cpre, G, M, N, K, act, gather, gather_rows, row_scale, stream);
     }
 }
 
@@ -328,8 +336,9 @@ gemm_f32_kernel(const float* __restrict__ Ag, const float* __restrict__ Bg, floa
         }
 }
 
-static void launch_gemm_f32(const float* A, const float* B, float* C, float* Cpre, int G, int M, int N, int K,
-                            int act, hipStream_t stream) {
+static int launch_gemm_f32(const float* A, const float* B, float* C, float* Cpre, int G, int M, int N, int K,
+                           int act, hipStream_t stream) {
+    if ((M + 63) / 64 > 65535 || G > 65535) return EC_ERR_UNSUPPORTED;  // grid.y / grid.z limits
     dim3 grid((unsigned)((N + 63) / 64), (unsigned)((M + 63) / 64), (unsigned)G), block(256);
 #define EC_SGEMM_CASE(ACTV)                                                                         \
     if (Cpre) hipLaunchKernelGGL((gemm_f32_kernel<ACTV, true>), grid, block, 0, stream, A, B, C, Cpre, M, N, K); \
@@ -338,6 +347,7 @@ static void launch_gemm_f32(const float* A, const float* B, float* C, float* Cpr
     else if (act == EC_ACT_GELU) { EC_SGEMM_CASE(EC_ACT_GELU); }
     else { EC_SGEMM_CASE(EC_ACT_IDENTITY); }
 #undef EC_SGEMM_CASE
+    return check_launch();
 }
 
 // ---------------------------------------------------------------------------
@@ -345,35 +355,38 @@ static void launch_gemm_f32(const float* A, const float* B, float* C, float* Cpr
 // ---------------------------------------------------------------------------
 // True when the first product can gather its rows straight from X (no X_in buffer needed).
 bool ffn_can_gather(int dtype, int64_t n, int64_t k, int64_t d, int64_t d_ff) {
-    return dtype == EC_BF16 && (d % GEMM_BK) == 0 && n * d * 2 < ((int64_t)1 << 31) - 65536 &&
-           d * d_ff * 2 < ((int64_t)1 << 31) && k > 0;
+    return dtype == EC_BF16 && k > 0 && gemm_bf16_fast_ok(k, d_ff, d, true, n);
+}
+// True when the second product can weight its output rows (the matrix-core kernel runs it).
+bool ffn_can_scale_rows(int dtype, int64_t k, int64_t d, int64_t d_ff) {
+    return dtype == EC_BF16 && k > 0 && gemm_bf16_fast_ok(k, d, d_ff, false, 0);
 }
 
 // Xin == nullptr: gather mode, rows of the buckets are read from X through I (needs ffn_can_gather).
+// xe_row_scale (optional, [e*k], needs ffn_can_scale_rows): X_e[i,j,:] is multiplied by xe_row_scale[i*k+j] in fp32
+// before its rounding -- the gate weight of Eq. 4 applied where the row is produced.
 int launch_ffn(const void* Xin, const void* X, const int32_t* I, int64_t n, const void* W1, const void* W2, void* Xe,
                void* A_save, void* H, int64_t e, int64_t k, int64_t d, int64_t d_ff, int act, int dtype,
-               hipStream_t stream) {
+               hipStream_t stream, const float* xe_row_scale) {
     const int G = (int)e, M = (int)k;
     if (dtype == EC_BF16) {
+        int rc;
         if (Xin == nullptr)
-            gemm_bf16_dispatch((const bf16_t*)X, (const bf16_t*)W1, (bf16_t*)H, (bf16_t*)A_save, G, M, (int)d_ff, (int)d,
-                               act, I, (int)n, stream);
+            rc = gemm_bf16_dispatch((const bf16_t*)X, (const bf16_t*)W1, (bf16_t*)H, (bf16_t*)A_save, G, M, (int)d_ff,
+                                    (int)d, act, I, (int)n, nullptr, stream);
         else
-            gemm_bf16_dispatch((const bf16_t*)Xin, (const bf16_t*)W1, (bf16_t*)H, (bf16_t*)A_save, G, M, (int)d_ff,
-                               (int)d, act, nullptr, 0, stream);
-        int rc = check_launch();
+            rc = gemm_bf16_dispatch((const bf16_t*)Xin, (const bf16_t*)W1, (bf16_t*)H, (bf16_t*)A_save, G, M, (int)d_ff,
+                                    (int)d, act, nullptr, 0, nullptr, stream);
         if (rc != EC_OK) return rc;
-        gemm_bf16_dispatch((const bf16_t*)H, (const bf16_t*)W2, (bf16_t*)Xe, nullptr, G, M, (int)d, (int)d_ff,
-                           EC_ACT_IDENTITY, nullptr, 0, stream);
-        return check_launch();
+        return gemm_bf16_dispatch((const bf16_t*)H, (const bf16_t*)W2, (bf16_t*)Xe, nullptr, G, M, (int)d, (int)d_ff,
+                                  EC_ACT_IDENTITY, nullptr, 0, xe_row_scale, stream);
     }
-    launch_gemm_f32((const float*)Xin, (const float*)W1, (float*)H, (float*)A_save, G, M, (int)d_ff, (int)d, act,
-                    stream);
-    int rc = check_launch();
+    if (Xin == nullptr || xe_row_scale != nullptr) return EC_ERR_UNSUPPORTED;
+    int rc = launch_gemm_f32((const float*)Xin, (const float*)W1, (float*)H, (float*)A_save, G, M, (int)d_ff, (int)d, act,
+                             stream);
     if (rc != EC_OK) return rc;
-    launch_gemm_f32((const float*)H, (const float*)W2, (float*)Xe, nullptr, G, M, (int)d, (int)d_ff,
-                    EC_ACT_IDENTITY, stream);
-    return check_launch();
+    return launch_gemm_f32((const float*)H, (const float*)W2, (float*)Xe, nullptr, G, M, (int)d, (int)d_ff,
+                           EC_ACT_IDENTITY, stream);
 }
 
 }  // namespace ecmoe

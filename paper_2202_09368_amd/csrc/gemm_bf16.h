@@ -22,6 +22,8 @@
 // LDS and stores full 16-byte vectors.
 #pragma once
 
+#include <atomic>
+
 #include "ec_common.h"
 
 namespace ecmoe {
@@ -32,9 +34,10 @@ constexpr int GEMM_LDS_STRIDE = GEMM_BK + 8;  // bf16 elements per LDS row of a 
 typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
 
 enum GemmEpilogue {
-    EPI_ACT = 0,       // C (bf16) = act(acc)
+    EPI_ACT = 0,       // C (bf16) = act(acc) [* row_scale[m]]
     EPI_ACT_SAVE = 1,  // additionally C2 (bf16) = acc
-    EPI_MULGRAD = 2,   // C (bf16) = acc * act'(C2[m][n]),  C2 = bf16 pre-activations (read)
+    EPI_MULGRAD = 2,   // C (bf16) = v = acc * act'(C2[m][n]) [* row_scale[m]],  C2 = bf16 pre-activations (read);
+                       // optionally C3 (bf16) = v - C, the part of v that the rounding of C dropped
     EPI_F32 = 3,       // C (fp32) = acc
     EPI_SOFTMAX = 4    // one group, N <= BN: C (fp32, [N][M]) = softmax over n of acc[m][:], transposed;
                        // C2 (fp32, [M][N], optional) the same untransposed.  `gather` is not used for
@@ -81,11 +84,16 @@ __device__ __forceinline__ float apply_act_grad_bf16(float a) {
     return 1.0f;
 }
 
-template <int BM, int BN, int STAGES, int OCC, bool A_MC, bool B_KC, int EPI, int ACT>
+// SPLIT_A (A_MC = false only): the left operand is the sum of two bf16 matrices, A[g] + A2[g] (a value carried as
+// high part + remainder); the contraction runs over both in turn against the same B, so the product sees the
+// left operand to 2^-17 at twice the work.
+template <int BM, int BN, int STAGES, int OCC, bool A_MC, bool B_KC, int EPI, int ACT, bool SPLIT_A = false>
 __global__ void __launch_bounds__(256, OCC)
 gemm_bf16_kernel(const bf16_t* __restrict__ Aall, const bf16_t* __restrict__ Ball, void* __restrict__ Call,
                  void* __restrict__ C2all, int M, int N, int K, int G, int tiles_m, int tiles_n,
-                 const int32_t* __restrict__ gather, int gather_rows) {
+                 const int32_t* __restrict__ gather, int gather_rows, const float* __restrict__ row_scale,
+                 const bf16_t* __restrict__ A2all, void* __restrict__ C3all) {
+    static_assert(!SPLIT_A || !A_MC, "the two-part left operand is contraction-contiguous");
     constexpr int WM = BM / 2, WN = BN / 2;
     constexpr int TM = WM / 32, TN = WN / 32;
     constexpr int A_CHUNKS = BM / 32, B_CHUNKS = BN / 32;  // 16-byte chunks per thread and stage
@@ -136,6 +144,9 @@ gemm_bf16_kernel(const bf16_t* __restrict__ Aall, const bf16_t* __restrict__ Bal
     const __amdgpu_buffer_rsrc_t rsrcA = (!A_MC && gather != nullptr)
         ? __builtin_amdgcn_make_buffer_rsrc(const_cast<bf16_t*>(Aall), 0, gather_rows * K * 2, 0x00020000)
         : __builtin_amdgcn_make_buffer_rsrc(const_cast<bf16_t*>(Aall + (size_t)g * M * K), 0, M * K * 2, 0x00020000);
+    const __amdgpu_buffer_rsrc_t rsrcA2 = SPLIT_A
+        ? __builtin_amdgcn_make_buffer_rsrc(const_cast<bf16_t*>(A2all + (size_t)g * M * K), 0, M * K * 2, 0x00020000)
+        : rsrcA;
     const __amdgpu_buffer_rsrc_t rsrcB = __builtin_amdgcn_make_buffer_rsrc(
         const_cast<bf16_t*>(Ball + (size_t)g * K * N), 0, K * N * 2, 0x00020000);
     const int a_kstep = A_MC ? M * 2 : 2;  // bytes per unit of k in the scalar stage offset
@@ -187,13 +198,18 @@ gemm_bf16_kernel(const bf16_t* __restrict__ Aall, const bf16_t* __restrict__ Bal
 
     u32x4 areg[A_CHUNKS];
     u32x4 breg[B_CHUNKS];
+    // Stage at contraction offset k0.  With a two-part left operand, offsets K..2K-1 address the second part
+    // (and the same B rows as k0 - K).
     auto load_tiles = [&](int k0) {
+        const bool second = SPLIT_A && k0 >= K;
+        const int kk = second ? k0 - K : k0;
 #pragma unroll
         for (int r = 0; r < A_CHUNKS; ++r)
-            areg[r] = __builtin_amdgcn_raw_buffer_load_b128(rsrcA, a_voff[r], k0 * a_kstep, 0);
+            areg[r] = second ? __builtin_amdgcn_raw_buffer_load_b128(rsrcA2, a_voff[r], kk * a_kstep, 0)
+                             : __builtin_amdgcn_raw_buffer_load_b128(rsrcA, a_voff[r], kk * a_kstep, 0);
 #pragma unroll
         for (int r = 0; r < B_CHUNKS; ++r)
-            breg[r] = __builtin_amdgcn_raw_buffer_load_b128(rsrcB, b_voff[r], k0 * b_kstep, 0);
+            breg[r] = __builtin_amdgcn_raw_buffer_load_b128(rsrcB, b_voff[r], kk * b_kstep, 0);
     };
     auto store_tiles = [&](int buf) {
         bf16_t* base = smem + buf * STAGE;
@@ -261,9 +277,13 @@ gemm_bf16_kernel(const bf16_t* __restrict__ Aall, const bf16_t* __restrict__ Bal
         else if (r < N_CHUNKS) *reinterpret_cast<u32x4*>(&dst[b_lds[r - A_CHUNKS]]) = breg[r - A_CHUNKS];
     };
     auto stage_load = [&](int r, int k_next) {
-        if (r < A_CHUNKS) areg[r] = __builtin_amdgcn_raw_buffer_load_b128(rsrcA, a_voff[r], k_next * a_kstep, 0);
+        const bool second = SPLIT_A && k_next >= K;
+        const int kk = second ? k_next - K : k_next;
+        if (r < A_CHUNKS)
+            areg[r] = second ? __builtin_amdgcn_raw_buffer_load_b128(rsrcA2, a_voff[r], kk * a_kstep, 0)
+                             : __builtin_amdgcn_raw_buffer_load_b128(rsrcA, a_voff[r], kk * a_kstep, 0);
         else if (r < N_CHUNKS)
-            breg[r - A_CHUNKS] = __builtin_amdgcn_raw_buffer_load_b128(rsrcB, b_voff[r - A_CHUNKS], k_next * b_kstep, 0);
+            breg[r - A_CHUNKS] = __builtin_amdgcn_raw_buffer_load_b128(rsrcB, b_voff[r - A_CHUNKS], kk * b_kstep, 0);
     };
     // One step (16 contraction elements) written in issue order.  After every MFMA comes at most one
     // fragment read for the following step (taken from `next_stage` at step `next_s`) and, in the
@@ -290,7 +310,8 @@ gemm_bf16_kernel(const bf16_t* __restrict__ Aall, const bf16_t* __restrict__ Bal
     };
 
     // Loads past the last stage read zeros or in-range data of the same group: harmless, never consumed.
-    const int nk = (K + GEMM_BK - 1) / GEMM_BK;  // a ragged K is legal only when both operands keep k as the row index
+    // a ragged K is legal only when both operands keep k as the row index; a two-part left operand doubles the stages
+    const int nk = (SPLIT_A ? 2 : 1) * ((K + GEMM_BK - 1) / GEMM_BK);
     load_tiles(0);
     if (STAGES == 2) {
         store_tiles(0);
@@ -407,6 +428,13 @@ gemm_bf16_kernel(const bf16_t* __restrict__ Aall, const bf16_t* __restrict__ Bal
             bf16_t* __restrict__ dst = pre ? Cpre : C;
 #pragma unroll
             for (int i = 0; i < TM; ++i) {
+                // optional weight of the output row this lane holds (the gate value of a bucket row), applied to
+                // the fp32 result before its one rounding
+                float rs = 1.0f;
+                if (EPI == EPI_ACT && row_scale != nullptr) {
+                    const int gm = m0 + wr * WM + i * 32 + col;
+                    rs = row_scale[(size_t)g * M + (gm < M ? gm : M - 1)];
+                }
 #pragma unroll
                 for (int j = 0; j < TN; ++j)
 #pragma unroll
@@ -415,7 +443,7 @@ gemm_bf16_kernel(const bf16_t* __restrict__ Aall, const bf16_t* __restrict__ Bal
 #pragma unroll
                         for (int t = 0; t < 4; ++t) {
                             const float x = acc[i][j][4 * q + t];
-                            v[t] = static_cast<bf16_t>(pre ? x : apply_act_bf16<ACT>(x));
+                            v[t] = static_cast<bf16_t>(pre ? x : (EPI == EPI_ACT ? rs * apply_act_bf16<ACT>(x) : apply_act_bf16<ACT>(x)));
                         }
                         *reinterpret_cast<bf16x4*>(&strip[col * EPI_STRIDE + j * 32 + 8 * q + 4 * half]) = v;
                     }
@@ -463,6 +491,7 @@ gemm_bf16_kernel(const bf16_t* __restrict__ Aall, const bf16_t* __restrict__ Bal
                 }
             } else {
                 bf16_t* __restrict__ C = reinterpret_cast<bf16_t*>(Call) + gofs;
+                bf16_t* __restrict__ Clo = C3all != nullptr ? reinterpret_cast<bf16_t*>(C3all) + gofs : nullptr;
                 const bf16_t* __restrict__ Aux = reinterpret_cast<const bf16_t*>(C2all) + gofs;
                 constexpr int CHUNKS_PER_ROW = WN / 8;
                 constexpr int ROWS_PER_PASS = 64 / CHUNKS_PER_ROW;
@@ -476,13 +505,19 @@ gemm_bf16_kernel(const bf16_t* __restrict__ Aall, const bf16_t* __restrict__ Bal
                         const floatx4 v0 = *reinterpret_cast<const floatx4*>(&strip[row * EPI_STRIDE + ec * 8]);
                         const floatx4 v1 = *reinterpret_cast<const floatx4*>(&strip[row * EPI_STRIDE + ec * 8 + 4]);
                         const bf16x8 a = *reinterpret_cast<const bf16x8*>(Aux + (size_t)gm * N + gn);
-                        bf16x8 o;
+                        const float rs = row_scale != nullptr ? row_scale[(size_t)g * M + gm] : 1.0f;
+                        bf16x8 o, lo;
 #pragma unroll
                         for (int t = 0; t < 4; ++t) {
-                            o[t] = static_cast<bf16_t>(v0[t] * apply_act_grad_bf16<ACT>(static_cast<float>(a[t])));
-                            o[t + 4] = static_cast<bf16_t>(v1[t] * apply_act_grad_bf16<ACT>(static_cast<float>(a[t + 4])));
+                            const float w0 = (rs * v0[t]) * apply_act_grad_bf16<ACT>(static_cast<float>(a[t]));
+                            const float w1 = (rs * v1[t]) * apply_act_grad_bf16<ACT>(static_cast<float>(a[t + 4]));
+                            o[t] = static_cast<bf16_t>(w0);
+                            o[t + 4] = static_cast<bf16_t>(w1);
+                            lo[t] = static_cast<bf16_t>(w0 - static_cast<float>(o[t]));
+                            lo[t + 4] = static_cast<bf16_t>(w1 - static_cast<float>(o[t + 4]));
                         }
                         *reinterpret_cast<bf16x8*>(C + (size_t)gm * N + gn) = o;
+                        if (Clo != nullptr) *reinterpret_cast<bf16x8*>(Clo + (size_t)gm * N + gn) = lo;
                     }
                 }
             }
@@ -511,18 +546,31 @@ inline bool gemm_bf16_shape_ok(int64_t M, int64_t N, int64_t K, bool k_contiguou
            M * K * 2 < ((int64_t)1 << 31) && K * N * 2 < ((int64_t)1 << 31) && M * N < ((int64_t)1 << 31);
 }
 
-template <int BM, int BN, int STAGES, int OCC, bool A_MC, bool B_KC, int EPI, int ACT>
+// Raises a kernel's dynamic-LDS limit once per kernel and GPU (the attribute belongs to the function on the
+// current device); `done` is the instantiation's own flag array.
+inline void gemm_allow_lds(const void* kern, size_t lds, std::atomic<bool>* done /*[64]*/) {
+    if (lds <= 64 * 1024) return;
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) dev = 0;
+    if (done[dev].load(std::memory_order_acquire)) return;
+    (void)hipFuncSetAttribute(kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+    done[dev].store(true, std::memory_order_release);
+}
+
+// A2 (with SPLIT_A): the second part of the left operand.  C3 (EPI_MULGRAD, optional): receives what the rounding of C
+// dropped.
+template <int BM, int BN, int STAGES, int OCC, bool A_MC, bool B_KC, int EPI, int ACT, bool SPLIT_A = false>
 static void gemm_bf16_launch(const bf16_t* A, const bf16_t* B, void* C, void* C2, int G, int M, int N, int K,
-                             const int32_t* gather, int gather_rows, hipStream_t stream) {
+                             const int32_t* gather, int gather_rows, hipStream_t stream,
+                             const float* row_scale = nullptr, const bf16_t* A2 = nullptr, void* C3 = nullptr) {
     const int tiles_m = (M + BM - 1) / BM, tiles_n = (N + BN - 1) / BN;
     const int total = G * tiles_m * tiles_n;
     const size_t lds = gemm_bf16_lds_bytes<BM, BN, STAGES>();
-    auto kern = gemm_bf16_kernel<BM, BN, STAGES, OCC, A_MC, B_KC, EPI, ACT>;
-    if (lds > 64 * 1024)
-        (void)hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
-                                  (int)lds);
+    auto kern = gemm_bf16_kernel<BM, BN, STAGES, OCC, A_MC, B_KC, EPI, ACT, SPLIT_A>;
+    static std::atomic<bool> lds_allowed[64];
+    gemm_allow_lds(reinterpret_cast<const void*>(kern), lds, lds_allowed);
     hipLaunchKernelGGL(kern, dim3((unsigned)((total + 7) / 8 * 8)), dim3(256), lds, stream, A, B, C, C2, M, N, K, G,
-                       tiles_m, tiles_n, gather, gather_rows);
+                       tiles_m, tiles_n, gather, gather_rows, row_scale, A2, C3);
 }
 
 }  // namespace ecmoe

@@ -7,6 +7,13 @@ import torch
 import workloads as wl
 
 
+def sized(base: wl.Workload, **kw) -> wl.Workload:
+    """A resized copy of a workload with k taken from the library's own host function (Eq. 1)."""
+    import paper_2202_09368_amd as m
+    w = wl.scaled(base, **kw)
+    return w if w.k is not None else wl.scaled(w, k=m.ec_moe_capacity(w.n, w.e, w.c))
+
+
 def to_dev(a: np.ndarray) -> torch.Tensor:
     """numpy (float32 / int32 / uint16 bf16 bits) -> tensor on cuda:0 (bf16 for uint16)."""
     if a.dtype == np.uint16:

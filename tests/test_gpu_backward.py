@@ -8,7 +8,7 @@ import workloads as wl
 import os
 import time
 
-from gpu_util import max_rel_err, max_rel_err_rows, score_tolerance, to_dev, to_f64, to_host, torch_dtype
+from gpu_util import sized, max_rel_err, max_rel_err_rows, score_tolerance, to_dev, to_f64, to_host, torch_dtype
 
 pytestmark = pytest.mark.gpu
 
@@ -57,15 +57,15 @@ def _forward_backward(m, w, inp, keep_on_device=False):
 
 
 @pytest.mark.parametrize("name,kw,tol", [
-    ("cfg1", dict(n=300, d=60, e=5, c=2.0, d_ff=100), 2e-4),                      # fp32, ragged everything
-    ("cfg1", dict(n=256, d=64, e=8, c=2.0, d_ff=256, act=wl.ACT_GELU), 2e-4),     # fp32, GeLU
+    ("cfg1", dict(n=300, d=60, e=5, c=2.0, d_ff=100), 1e-5),                      # fp32, ragged everything
+    ("cfg1", dict(n=256, d=64, e=8, c=2.0, d_ff=256, act=wl.ACT_GELU), 1e-5),     # fp32, GeLU
     ("cfg2", dict(n=1000, d=192, e=16, d_ff=320), 2e-2),                          # bf16 matrix-core path, k = 125
     ("cfg2", dict(n=2048, d=256, e=8, d_ff=512, act=wl.ACT_RELU), 2e-2),          # bf16, ReLU
     ("cfg2", dict(n=1000, d=192, e=16, d_ff=328), 2e-2),                          # bf16, d_ff % 64 != 0: plain path
     ("cfg3", dict(n=4096, d=128, e=64, d_ff=256), 2e-2),                          # bf16, 64 experts (CSR lists)
 ])
 def test_backward_reduced(m, ref, name, kw, tol):
-    w = wl.scaled(wl.WORKLOADS[name], backward=True, **kw)
+    w = sized(wl.WORKLOADS[name], backward=True, **kw)
     inp = wl.make_inputs(w)
     print(f"[bwd {w.name}] n={w.n} d={w.d} e={w.e} k={w.k} d_ff={w.d_ff} act={w.act}", flush=True)
     r = _forward_backward(m, w, inp)
@@ -75,7 +75,7 @@ def test_backward_reduced(m, ref, name, kw, tol):
         err = max_rel_err(r[key], g[key])
         print(f"[bwd {w.name}] {key} max rel err {err:.3e}", flush=True)
         errs[key] = err
-    assert all(v <= (1.5 * tol if key == "dX" else tol) for key, v in errs.items()), errs
+    assert all(v <= tol for v in errs.values()), errs
 
 
 def _progress(msg):
@@ -97,11 +97,13 @@ def test_cfg4_full_forward_backward(m, ref):
 
     _progress("scores and selection")
     S_ref = ref.gate(inp["X"], inp["Wg"])
-    assert (max_rel_err_rows(S, S_ref) <= score_tolerance(inp["X"], inp["Wg"])).all()
+    s_err = max_rel_err_rows(S, S_ref)
+    _progress(f"S max rel err {s_err.max():.3e} (bar 1e-5)")
+    assert s_err.max() <= 1e-5
     G_o, I_o = ref.topk_tokens(S, k)
     assert (I_o == I).all() and (G_o.view(np.uint32) == G.view(np.uint32)).all()
 
-    ex = [0, 77, 127]
+    ex = [0, 13, 31, 50, 77, 90, 111, 127]
     _progress(f"oracle FFN forward/backward on experts {ex}")
     Xin_ex = ref.dispatch(inp["X"], I[ex])
     Xe_ref = ref.expert_ffn(Xin_ex, inp["W1"][ex], inp["W2"][ex], w.act)
@@ -136,4 +138,4 @@ def test_cfg4_full_forward_backward(m, ref):
             dX_ref[I[i, j], :] += dXin_ref[a, j, :]
     err = max_rel_err(to_f64(to_host(r["dX"]))[toks], dX_ref[toks])
     _progress(f"dX on {toks.size} tokens served only by the sample: max rel err {err:.3e}")
-    assert err <= 3e-2
+    assert err <= 2e-2

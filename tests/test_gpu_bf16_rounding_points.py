@@ -39,7 +39,7 @@ def _round_bf16(a):
     (1025, dict(n=1000, d=128, e=128, c=0.5, d_ff=328, act=wl.ACT_IDENTITY)),
 ])
 def test_bf16_layer_against_the_same_rounding_points(m, ref, seed, kw):
-    w = wl.Workload("rounding", dtype=wl.DTYPE_BF16, seed=seed, **kw)
+    w = wl.Workload("rounding", dtype=wl.DTYPE_BF16, seed=seed, k=m.ec_moe_capacity(kw["n"], kw["e"], kw["c"]), **kw)
     inp = wl.make_inputs(w)
     n, d, e, k = w.n, w.d, w.e, w.k
     print(f"[rounding points] n={n} d={d} e={e} k={k} d_ff={w.d_ff} act={w.act}", flush=True)

@@ -6,7 +6,7 @@ import pytest
 import torch
 
 import workloads as wl
-from gpu_util import max_rel_err, max_rel_err_rows, out_tol, score_tolerance, to_dev, to_host, torch_dtype
+from gpu_util import sized, max_rel_err, max_rel_err_rows, out_tol, score_tolerance, to_dev, to_host, torch_dtype
 
 pytestmark = pytest.mark.gpu
 
@@ -72,7 +72,7 @@ def test_capped_assignment(m, ref, n, e, k, b, lam, iters, scale):
     ("cfg2", dict(), 2.0, 100),                                          # full size, as `bench.py --capped 2` runs it
 ])
 def test_capped_forward(m, ref, base, kw, b, iters):
-    w = wl.scaled(wl.WORKLOADS[base], **kw)
+    w = sized(wl.WORKLOADS[base], **kw)
     inp = wl.make_inputs(w)
     n, d, e = w.n, w.d, w.e
     k = ref.capacity(n, w.c, e)

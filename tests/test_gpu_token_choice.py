@@ -5,7 +5,7 @@ import pytest
 import torch
 
 import workloads as wl
-from gpu_util import max_rel_err, max_rel_err_rows, out_tol, score_tolerance, to_dev, to_host, torch_dtype
+from gpu_util import sized, max_rel_err, max_rel_err_rows, out_tol, score_tolerance, to_dev, to_host, torch_dtype
 
 pytestmark = pytest.mark.gpu
 
@@ -98,7 +98,7 @@ def test_dispatch_and_combine_with_empty_rows(m, ref):
     ("cfg2", dict(), 2, 2.0),                                           # full size, as `bench.py --token-choice 2` runs it
 ])
 def test_token_choice_forward(m, ref, base, kw, m_top, c):
-    w = wl.scaled(wl.WORKLOADS[base], c=c, **kw)
+    w = sized(wl.WORKLOADS[base], c=c, **kw)
     inp = wl.make_inputs(w)
     n, d, e = w.n, w.d, w.e
     cap = ref.capacity(n, c, e)
@@ -140,14 +140,14 @@ def test_token_choice_forward(m, ref, base, kw, m_top, c):
 
 
 @pytest.mark.parametrize("base,kw,tol", [
-    ("cfg1", dict(n=256, d=64, e=8, c=2.0, d_ff=128, act=wl.ACT_GELU), 2e-4),
+    ("cfg1", dict(n=256, d=64, e=8, c=2.0, d_ff=128, act=wl.ACT_GELU), 1e-5),
     ("cfg2", dict(n=2048, d=256, e=16, d_ff=512), 2e-2),
     ("cfg3", dict(n=4096, d=256, e=32, d_ff=512), 2e-2),        # CSR combine index, many empty rows and drops
 ])
 def test_token_choice_backward(m, ref, base, kw, tol):
     # the forward keeps what the backward consumes; ec_moe_backward then runs on buffers with dropped tokens
     # and empty rows, against the oracle's backward on the same routing
-    w = wl.scaled(wl.WORKLOADS[base], backward=True, **kw)
+    w = sized(wl.WORKLOADS[base], backward=True, **kw)
     inp = wl.make_inputs(w)
     n, d, e, f = w.n, w.d, w.e, w.d_ff
     cap = ref.capacity(n, w.c, e)
@@ -180,4 +180,4 @@ def test_token_choice_backward(m, ref, base, kw, tol):
     for key, got in (("dX", dX), ("dWg", dWg), ("dW1", dW1), ("dW2", dW2)):
         err = max_rel_err(to_host(got), g[key])
         _p(f"[token choice backward] {key} max rel err {err:.3e}")
-        assert err <= (1.5 * tol if key == "dX" else tol)
+        assert err <= tol

@@ -18,6 +18,12 @@ import workloads as wl
 from oracle import ec_moe_ref as ref
 
 
+def _sized(base, **kw):
+    """A resized copy of a workload with k from the oracle's Eq. 1."""
+    w = wl.scaled(base, **kw)
+    return w if w.k is not None else wl.scaled(w, k=ref.capacity(w.n, w.c, w.e))
+
+
 def _rng(seed):
     return np.random.default_rng(seed)
 
@@ -509,7 +515,7 @@ def test_grouped_topk_special_cases():
 @pytest.mark.parametrize("act", [wl.ACT_GELU, wl.ACT_IDENTITY])
 def test_grouped_layer_is_the_plain_layer_on_every_group(act):
     # routing per group == running Eq. 1-4 on each group as a batch of its own
-    w = wl.scaled(wl.WORKLOADS["cfg1"], n=48, d=8, e=4, c=2.0, d_ff=16, act=act, seed=21)
+    w = _sized(wl.WORKLOADS["cfg1"], n=48, d=8, e=4, c=2.0, d_ff=16, act=act, seed=21)
     inp = wl.make_inputs(w)
     groups = 4
     n_g = w.n // groups
@@ -601,7 +607,7 @@ def test_token_choice_invariants_and_priority():
 
 def test_token_choice_layer_without_drops_is_dense_top_m_mixture():
     # buffers as large as the batch: nothing is dropped, X_out[l] = sum over l's top-m experts of S[l,i] FFN_i(x_l)
-    w = wl.scaled(wl.WORKLOADS["cfg1"], n=24, d=8, e=4, d_ff=12, act=wl.ACT_GELU, seed=9)
+    w = _sized(wl.WORKLOADS["cfg1"], n=24, d=8, e=4, d_ff=12, act=wl.ACT_GELU, seed=9)
     inp = wl.make_inputs(w)
     m = 2
     out = ref.forward_token_choice(inp["X"], inp["Wg"], inp["W1"], inp["W2"], c=float(w.e), m=m, act=w.act)
@@ -693,7 +699,7 @@ def test_capped_assignment_special_cases():
     A0 = ref.capped_assignment(np.array([[0.0, 0.001]], np.float32), 1, 1, lam=1e-3, iters=0, out_dtype=np.float64)
     np.testing.assert_allclose(A0.ravel(), [1.0, math.e], rtol=1e-6)
     # layer: with the cap slack and the solver run to the end, the buckets are those of plain expert choice
-    w = wl.scaled(wl.WORKLOADS["cfg1"], n=32, d=8, e=4, d_ff=12, act=wl.ACT_GELU, seed=13)
+    w = _sized(wl.WORKLOADS["cfg1"], n=32, d=8, e=4, d_ff=12, act=wl.ACT_GELU, seed=13)
     inp = wl.make_inputs(w)
     plain = ref.forward(inp["X"], inp["Wg"], inp["W1"], inp["W2"], w.c, w.act)
     capped = ref.forward_capped(inp["X"], inp["Wg"], inp["W1"], inp["W2"], w.c, w.act, b=float(w.e * plain["k"]),
@@ -712,7 +718,7 @@ def test_workload_generators_are_seeded_and_shaped():
     assert a["X"].shape == (256, 64) and a["Wg"].shape == (64, 8)
     assert a["W1"].shape == (8, 64, 256) and a["W2"].shape == (8, 256, 64)
     assert abs(a["Wg"].std() - 1 / 8) < 0.01 and abs(a["W2"].std() - 1 / 16) < 0.01
-    s = wl.scaled(wl.WORKLOADS["cfg5"], n=2048, d=64, e=8)
+    s = _sized(wl.WORKLOADS["cfg5"], n=2048, d=64, e=8)
     t = wl.make_inputs(s)
     assert t["X"].dtype == np.uint16 and "W1" not in t and len(t["skew_rows"]) == 20
     # bf16 rounding: nearest-even on a few exact cases

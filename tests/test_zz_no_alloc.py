@@ -12,7 +12,7 @@ import torch
 
 import paper_2202_09368_amd as m
 import workloads as wl
-from tests.gpu_util import to_dev, to_host
+from gpu_util import to_dev, to_host
 
 pytestmark = pytest.mark.gpu
 

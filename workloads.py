@@ -40,29 +40,30 @@ class Workload:
     skew_frac: float = 0.0   # fraction of token rows multiplied by skew_scale
     skew_scale: float = 1.0
     backward: bool = False
-
-    @property
-    def k(self) -> int:
-        return int(np.floor(self.n * self.c / self.e))
+    k: Optional[int] = None  # tokens per expert: a number the caller supplies (the workload descriptions print it;
+                             # resized copies get it from whichever implementation is under test), never computed here
 
 
 # The five workloads the build is measured and parity-checked on.
 WORKLOADS: Dict[str, Workload] = {
     "cfg1": Workload("cfg1", n=256, d=64, e=8, c=2.0, d_ff=256, act=ACT_RELU,
-                     dtype=DTYPE_F32, seed=0),
+                     dtype=DTYPE_F32, seed=0, k=64),
     "cfg2": Workload("cfg2", n=8192, d=768, e=16, c=2.0, d_ff=3072, act=ACT_GELU,
-                     dtype=DTYPE_BF16, seed=2),
+                     dtype=DTYPE_BF16, seed=2, k=1024),
     "cfg3": Workload("cfg3", n=16384, d=1024, e=64, c=2.0, d_ff=4096, act=ACT_GELU,
-                     dtype=DTYPE_BF16, seed=3),
+                     dtype=DTYPE_BF16, seed=3, k=512),
     "cfg4": Workload("cfg4", n=32768, d=2048, e=128, c=2.0, d_ff=8192, act=ACT_GELU,
-                     dtype=DTYPE_BF16, seed=4, backward=True),
+                     dtype=DTYPE_BF16, seed=4, backward=True, k=512),
     "cfg5": Workload("cfg5", n=65536, d=4096, e=256, c=1.0, d_ff=0, act=ACT_IDENTITY,
-                     dtype=DTYPE_BF16, seed=5, skew_frac=0.01, skew_scale=10.0),
+                     dtype=DTYPE_BF16, seed=5, skew_frac=0.01, skew_scale=10.0, k=256),
 }
 
 
 def scaled(w: Workload, **kw) -> Workload:
-    """A copy of a workload with some fields replaced (reduced parity sizes)."""
+    """A copy of a workload with some fields replaced (reduced parity sizes).  When n, e or c change the
+    stored k no longer applies: pass the new k, or it is left unset for the caller to fill in."""
+    if "k" not in kw and any(key in kw and kw[key] != getattr(w, key) for key in ("n", "e", "c")):
+        kw["k"] = None
     return replace(w, **kw)
 
 
