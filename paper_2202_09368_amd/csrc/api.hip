@@ -224,16 +224,9 @@ static int forward_impl(const void* X, const void* Wg, const void* W1, const voi
     }
     void* H = H_out ? H_out : at(ws, L.h);
     void* Xe = Xe_out ? Xe_out : at(ws, L.xe);
-    // Eq. 4's weight G[i,j] is applied in the second product's epilogue (fp32, before the row's one rounding) when
-    // nobody asks for X_e itself; the combine is then a plain expert-ordered sum of rows.
-#ifndef EC_MOE_SCALE_IN_EPILOGUE
-#define EC_MOE_SCALE_IN_EPILOGUE 0
-#endif
-    const bool scaled_rows = EC_MOE_SCALE_IN_EPILOGUE && Xe_out == nullptr && ffn_can_scale_rows(dtype, k, d, d_ff);
-    rc = launch_ffn(fused_gather ? nullptr : Xin, X, I, n, W1, W2, Xe, A_out, H, e, k, d, d_ff, act, dtype, st,
-                    scaled_rows ? G : nullptr);
+    rc = launch_ffn(fused_gather ? nullptr : Xin, X, I, n, W1, W2, Xe, A_out, H, e, k, d, d_ff, act, dtype, st);
     if (rc != EC_OK) return rc;
-    return launch_combine(Xe, scaled_rows ? nullptr : G, I, Xout, n, d, e, k, dtype, ix, st);
+    return launch_combine(Xe, G, I, Xout, n, d, e, k, dtype, ix, st);
 }
 
 int ec_moe_forward(const void* X, const void* Wg, const void* W1, const void* W2, double c, void* Xout,

@@ -103,10 +103,9 @@ int launch_combine_index(const int32_t* I, int64_t n, int64_t e, int64_t k, cons
 int launch_dispatch(const void* X, const int32_t* I, void* Xin, int64_t n, int64_t d, int64_t e, int64_t k,
                     int dtype, hipStream_t stream);
 bool ffn_can_gather(int dtype, int64_t n, int64_t k, int64_t d, int64_t d_ff);
-bool ffn_can_scale_rows(int dtype, int64_t k, int64_t d, int64_t d_ff);
 int launch_ffn(const void* Xin, const void* X, const int32_t* I, int64_t n, const void* W1, const void* W2, void* Xe,
                void* A_save, void* H, int64_t e, int64_t k, int64_t d, int64_t d_ff, int act, int dtype,
-               hipStream_t stream, const float* xe_row_scale = nullptr);
+               hipStream_t stream);
 int launch_combine_csr(const int32_t* I, int64_t n, int64_t e, int64_t k, const CombineIndex& ix, hipStream_t stream);
 int launch_combine(const void* Xe, const float* G, const int32_t* I, void* Xout, int64_t n, int64_t d,
                    int64_t e, int64_t k, int dtype, const CombineIndex& ix, hipStream_t stream,

@@ -213,23 +213,22 @@ static bool gemm_bf16_fast_ok(int64_t M, int64_t N, int64_t K, bool gather, int6
 
 template <int BM, int BN, int STAGES, int OCC>
 static int launch_gemm_bf16(const bf16_t* A, const bf16_t* B, bf16_t* C, bf16_t* Cpre, int G, int M, int N, int K,
-                            int act, const int32_t* gather, int gather_rows, const float* row_scale,
-                            hipStream_t stream) {
+                            int act, const int32_t* gather, int gather_rows, hipStream_t stream) {
     if (gemm_bf16_fast_ok(M, N, K, gather != nullptr, gather_rows)) {
 #define EC_GEMM_CASE(ACTV)                                                                                       \
     if (Cpre) gemm_bf16_launch<BM, BN, STAGES, OCC, false, false, EPI_ACT_SAVE, ACTV>(A, B, C, Cpre, G, M, N, K,  \
                                                                                      gather, gather_rows, stream); \
     else gemm_bf16_launch<BM, BN, STAGES, OCC, false, false, EPI_ACT, ACTV>(A, B, C, nullptr, G, M, N, K, gather,  \
-                                                                           gather_rows, stream, row_scale)
+                                                                           gather_rows, stream)
         if (act == EC_ACT_RELU) { EC_GEMM_CASE(EC_ACT_RELU); }
         else if (act == EC_ACT_GELU) { EC_GEMM_CASE(EC_ACT_GELU); }
         else { EC_GEMM_CASE(EC_ACT_IDENTITY); }
 #undef EC_GEMM_CASE
         return check_launch();
     }
-    // general shapes: predicated kernel, 128 x 128 tiles.  It reads its left operand as stored and knows no row
-    // weights: a caller that asked for either gets an error instead of a wrong product.
-    if (gather != nullptr || row_scale != nullptr) return EC_ERR_UNSUPPORTED;
+    // general shapes: predicated kernel, 128 x 128 tiles.  It reads its left operand as stored: a caller that asked
+    // for gathered rows gets an error instead of a wrong product.
+    if (gather != nullptr) return EC_ERR_UNSUPPORTED;
     if ((int64_t)M * K >= ((int64_t)1 << 31) || (int64_t)K * N >= ((int64_t)1 << 31) || (int64_t)M * N >= ((int64_t)1 << 31))
         return EC_ERR_UNSUPPORTED;
     constexpr int GBM = 128, GBN = 128;
@@ -259,8 +258,7 @@ static int launch_gemm_bf16(const bf16_t* A, const bf16_t* B, bf16_t* C, bf16_t*
 // Tile configuration of a grouped product: the candidate with the lowest estimated time, taken as
 // (rounds of 256 compute units) x (tile area) / (relative rate of that configuration).
 static int gemm_bf16_dispatch(const bf16_t* A, const bf16_t* B, bf16_t* C, bf16_t* Cpre, int G, int M, int N,
-                              int K, int act, const int32_t* gather, int gather_rows, const float* row_scale,
-                              hipStream_t stream) {
+                              int K, int act, const int32_t* gather, int gather_rows, hipStream_t stream) {
     auto cost = [&](int bm, int bn, int occ, double rate) {
         double tiles = (double)G * ((M + bm - 1) / bm) * ((N + bn - 1) / bn);
         double rounds = std::ceil(tiles / (256.0 * occ)) * occ;
@@ -277,11 +275,11 @@ static int gemm_bf16_dispatch(const bf16_t* A, const bf16_t* B, bf16_t* C, bf16_
     // K = 768: 98-102 us against 104-110 us for the 256 x 128 pairs)
     if (pick == 3 && K <= 768 && cost(128, 128, 2, 1.0) <= 1.25 * c0) pick = 2;
     switch (pick) {
-        case 0: return launch_gemm_bf16<256, 256, 2, 1>(A, B, C, Cpre, G, M, N, K, act, gather, gather_rows, row_scale, stream);
-        case 1: return launch_gemm_bf16<256, 128, 2, 1>(A, B, C, Cpre, G, M, N, K, act, gather, gather_rows, row_scale, stream);
-        case 2: return launch_gemm_bf16<128, 128, 1, 2>(A, B, C, Cpre, G, M, N, K, act, gather, gather_rows, row_scale, stream);
-        case 4: return launch_gemm_bf16<256, 192, 2, 1>(A, B, C, Cpre, G, M, N, K, act, gather, gather_rows, row_scale, stream);
-        default: return launch_gemm_bf16<256, 128, 1, 2>(A, B, C, Cpre, G, M, N, K, act, gather, gather_rows, row_scale, stream);
+        case 0: return launch_gemm_bf16<256, 256, 2, 1>(A, B, C, Cpre, G, M, N, K, act, gather, gather_rows, stream);
+        case 1: return launch_gemm_bf16<256, 128, 2, 1>(A, B, C, Cpre, G, M, N, K, act, gather, gather_rows, stream);
+        case 2: return launch_gemm_bf16<128, 128, 1, 2>(A, B, C, Cpre, G, M, N, K, act, gather, gather_rows, stream);
+        case 4: return launch_gemm_bf16<256, 192, 2, 1>(A, B, C, Cpre, G, M, N, K, act, gather, gather_rows, stream);
+        default: return launch_gemm_bf16<256, 128, 1, 2>(A, B, C, Cpre, G, M, N, K, act, gather, gather_rows, stream);
     }
 }
 
@@ -357,31 +355,26 @@ static int launch_gemm_f32(const float* A, const float* B, float* C, float* Cpre
 bool ffn_can_gather(int dtype, int64_t n, int64_t k, int64_t d, int64_t d_ff) {
     return dtype == EC_BF16 && k > 0 && gemm_bf16_fast_ok(k, d_ff, d, true, n);
 }
-// True when the second product can weight its output rows (the matrix-core kernel runs it).
-bool ffn_can_scale_rows(int dtype, int64_t k, int64_t d, int64_t d_ff) {
-    return dtype == EC_BF16 && k > 0 && gemm_bf16_fast_ok(k, d, d_ff, false, 0);
-}
+
 
 // Xin == nullptr: gather mode, rows of the buckets are read from X through I (needs ffn_can_gather).
-// xe_row_scale (optional, [e*k], needs ffn_can_scale_rows): X_e[i,j,:] is multiplied by xe_row_scale[i*k+j] in fp32
-// before its rounding -- the gate weight of Eq. 4 applied where the row is produced.
 int launch_ffn(const void* Xin, const void* X, const int32_t* I, int64_t n, const void* W1, const void* W2, void* Xe,
                void* A_save, void* H, int64_t e, int64_t k, int64_t d, int64_t d_ff, int act, int dtype,
-               hipStream_t stream, const float* xe_row_scale) {
+               hipStream_t stream) {
     const int G = (int)e, M = (int)k;
     if (dtype == EC_BF16) {
         int rc;
         if (Xin == nullptr)
             rc = gemm_bf16_dispatch((const bf16_t*)X, (const bf16_t*)W1, (bf16_t*)H, (bf16_t*)A_save, G, M, (int)d_ff,
-                                    (int)d, act, I, (int)n, nullptr, stream);
+                                    (int)d, act, I, (int)n, stream);
         else
             rc = gemm_bf16_dispatch((const bf16_t*)Xin, (const bf16_t*)W1, (bf16_t*)H, (bf16_t*)A_save, G, M, (int)d_ff,
-                                    (int)d, act, nullptr, 0, nullptr, stream);
+                                    (int)d, act, nullptr, 0, stream);
         if (rc != EC_OK) return rc;
         return gemm_bf16_dispatch((const bf16_t*)H, (const bf16_t*)W2, (bf16_t*)Xe, nullptr, G, M, (int)d, (int)d_ff,
-                                  EC_ACT_IDENTITY, nullptr, 0, xe_row_scale, stream);
+                                  EC_ACT_IDENTITY, nullptr, 0, stream);
     }
-    if (Xin == nullptr || xe_row_scale != nullptr) return EC_ERR_UNSUPPORTED;
+    if (Xin == nullptr) return EC_ERR_UNSUPPORTED;
     int rc = launch_gemm_f32((const float*)Xin, (const float*)W1, (float*)H, (float*)A_save, G, M, (int)d_ff, (int)d, act,
                              stream);
     if (rc != EC_OK) return rc;

@@ -34,7 +34,7 @@ constexpr int GEMM_LDS_STRIDE = GEMM_BK + 8;  // bf16 elements per LDS row of a 
 typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
 
 enum GemmEpilogue {
-    EPI_ACT = 0,       // C (bf16) = act(acc) [* row_scale[m]]
+    EPI_ACT = 0,       // C (bf16) = act(acc)
     EPI_ACT_SAVE = 1,  // additionally C2 (bf16) = acc
     EPI_MULGRAD = 2,   // C (bf16) = v = acc * act'(C2[m][n]) [* row_scale[m]],  C2 = bf16 pre-activations (read);
                        // optionally C3 (bf16) = v - C, the part of v that the rounding of C dropped
@@ -85,8 +85,8 @@ __device__ __forceinline__ float apply_act_grad_bf16(float a) {
 }
 
 // SPLIT_A (A_MC = false only): the left operand is the sum of two bf16 matrices, A[g] + A2[g] (a value carried as
-// high part + remainder); the contraction runs over both in turn against the same B, so the product sees the
-// left operand to 2^-17 at twice the work.
+// high part + remainder); the contraction takes 64 columns of one, then the same 64 columns of the other, against
+// the same rows of B, so the product sees the left operand to 2^-17 at twice the work.
 template <int BM, int BN, int STAGES, int OCC, bool A_MC, bool B_KC, int EPI, int ACT, bool SPLIT_A = false>
 __global__ void __launch_bounds__(256, OCC)
 gemm_bf16_kernel(const bf16_t* __restrict__ Aall, const bf16_t* __restrict__ Ball, void* __restrict__ Call,
@@ -198,11 +198,12 @@ gemm_bf16_kernel(const bf16_t* __restrict__ Aall, const bf16_t* __restrict__ Bal
 
     u32x4 areg[A_CHUNKS];
     u32x4 breg[B_CHUNKS];
-    // Stage at contraction offset k0.  With a two-part left operand, offsets K..2K-1 address the second part
-    // (and the same B rows as k0 - K).
+    // Stage at contraction offset k0.  With a two-part left operand the stages alternate between the parts: stages
+    // 2j and 2j+1 multiply the first and the second part's columns 64j.. by the same 64 rows of B, which the second
+    // of them finds in the cache.
     auto load_tiles = [&](int k0) {
-        const bool second = SPLIT_A && k0 >= K;
-        const int kk = second ? k0 - K : k0;
+        const bool second = SPLIT_A && ((k0 / GEMM_BK) & 1) != 0;
+        const int kk = SPLIT_A ? (k0 / (2 * GEMM_BK)) * GEMM_BK : k0;
 #pragma unroll
         for (int r = 0; r < A_CHUNKS; ++r)
             areg[r] = second ? __builtin_amdgcn_raw_buffer_load_b128(rsrcA2, a_voff[r], kk * a_kstep, 0)
@@ -277,8 +278,8 @@ gemm_bf16_kernel(const bf16_t* __restrict__ Aall, const bf16_t* __restrict__ Bal
         else if (r < N_CHUNKS) *reinterpret_cast<u32x4*>(&dst[b_lds[r - A_CHUNKS]]) = breg[r - A_CHUNKS];
     };
     auto stage_load = [&](int r, int k_next) {
-        const bool second = SPLIT_A && k_next >= K;
-        const int kk = second ? k_next - K : k_next;
+        const bool second = SPLIT_A && ((k_next / GEMM_BK) & 1) != 0;
+        const int kk = SPLIT_A ? (k_next / (2 * GEMM_BK)) * GEMM_BK : k_next;
         if (r < A_CHUNKS)
             areg[r] = second ? __builtin_amdgcn_raw_buffer_load_b128(rsrcA2, a_voff[r], kk * a_kstep, 0)
                              : __builtin_amdgcn_raw_buffer_load_b128(rsrcA, a_voff[r], kk * a_kstep, 0);
@@ -312,10 +313,19 @@ gemm_bf16_kernel(const bf16_t* __restrict__ Aall, const bf16_t* __restrict__ Bal
     // Loads past the last stage read zeros or in-range data of the same group: harmless, never consumed.
     // a ragged K is legal only when both operands keep k as the row index; a two-part left operand doubles the stages
     const int nk = (SPLIT_A ? 2 : 1) * ((K + GEMM_BK - 1) / GEMM_BK);
-    load_tiles(0);
     if (STAGES == 2) {
-        store_tiles(0);
+        // Both of the first two stages are requested at once (one trip to memory instead of two in a row): stage 0
+        // into a second set of registers that only lives here, stage 1 into the set the loop works with.
+        u32x4 areg0[A_CHUNKS], breg0[B_CHUNKS];
+#pragma unroll
+        for (int r = 0; r < A_CHUNKS; ++r) areg0[r] = __builtin_amdgcn_raw_buffer_load_b128(rsrcA, a_voff[r], 0, 0);
+#pragma unroll
+        for (int r = 0; r < B_CHUNKS; ++r) breg0[r] = __builtin_amdgcn_raw_buffer_load_b128(rsrcB, b_voff[r], 0, 0);
         load_tiles(GEMM_BK);
+#pragma unroll
+        for (int r = 0; r < A_CHUNKS; ++r) *reinterpret_cast<u32x4*>(&smem[a_lds[r]]) = areg0[r];
+#pragma unroll
+        for (int r = 0; r < B_CHUNKS; ++r) *reinterpret_cast<u32x4*>(&smem[b_lds[r]]) = breg0[r];
         __syncthreads();
         read_frags(0, smem, 0);
         for (int kc = 0; kc < nk; ++kc) {
@@ -332,6 +342,7 @@ gemm_bf16_kernel(const bf16_t* __restrict__ Aall, const bf16_t* __restrict__ Bal
         }
         __syncthreads();  // every wavefront is done with the tile buffers before the epilogue reuses them
     } else {
+        load_tiles(0);
         for (int kc = 0; kc < nk; ++kc) {
             store_tiles(0);  // the buffer is free: every wavefront passed the barrier that ends the previous phase
             __syncthreads();
@@ -428,13 +439,6 @@ gemm_bf16_kernel(const bf16_t* __restrict__ Aall, const bf16_t* __restrict__ Bal
             bf16_t* __restrict__ dst = pre ? Cpre : C;
 #pragma unroll
             for (int i = 0; i < TM; ++i) {
-                // optional weight of the output row this lane holds (the gate value of a bucket row), applied to
-                // the fp32 result before its one rounding
-                float rs = 1.0f;
-                if (EPI == EPI_ACT && row_scale != nullptr) {
-                    const int gm = m0 + wr * WM + i * 32 + col;
-                    rs = row_scale[(size_t)g * M + (gm < M ? gm : M - 1)];
-                }
 #pragma unroll
                 for (int j = 0; j < TN; ++j)
 #pragma unroll
@@ -443,7 +447,7 @@ gemm_bf16_kernel(const bf16_t* __restrict__ Aall, const bf16_t* __restrict__ Bal
 #pragma unroll
                         for (int t = 0; t < 4; ++t) {
                             const float x = acc[i][j][4 * q + t];
-                            v[t] = static_cast<bf16_t>(pre ? x : (EPI == EPI_ACT ? rs * apply_act_bf16<ACT>(x) : apply_act_bf16<ACT>(x)));
+                            v[t] = static_cast<bf16_t>(pre ? x : apply_act_bf16<ACT>(x));
                         }
                         *reinterpret_cast<bf16x4*>(&strip[col * EPI_STRIDE + j * 32 + 8 * q + 4 * half]) = v;
                     }

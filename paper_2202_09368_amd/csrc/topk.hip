@@ -15,6 +15,8 @@
 //   4. every wavefront owns a contiguous range of tokens: count the admitted
 //      ones per range, prefix the counts, then write the bucket in ascending
 //      token order with ballot ranks.  No sort is needed.
+#include <atomic>
+
 #include "ec_common.h"
 
 namespace ecmoe {
@@ -677,9 +679,17 @@ int launch_topk(const float* St, int64_t n, int64_t e, int64_t k, float* G, int3
     dim3 grid((unsigned)e), block(TOPK_THREADS);
     if (staged) {
         auto kern = topk_tokens_kernel<true>;
-        if (dyn > 64 * 1024)
-            (void)hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
-                                      (int)dyn);
+        if (dyn > 64 * 1024) {
+            // the limit is raised once per GPU, to the whole budget, so later launches of any size are covered
+            static std::atomic<bool> raised[64];
+            int dev = 0;
+            if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) dev = 0;
+            if (!raised[dev].load(std::memory_order_acquire)) {
+                (void)hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
+                                          (int)topk_lds_budget());
+                raised[dev].store(true, std::memory_order_release);
+            }
+        }
         hipLaunchKernelGGL(kern, grid, block, dyn, stream, St, (int)n, (int)k, G, I, emit);
     } else {
         hipLaunchKernelGGL(topk_tokens_kernel<false>, grid, block, 0, stream, St, (int)n, (int)k, G, I, emit);

@@ -114,3 +114,53 @@ def test_capped_forward(m, ref, base, kw, b, iters):
     err = max_rel_err(to_host(Xout), ref.combine(Xe_ref, G_h, I_h, n))
     _p(f"[capped forward] X_out max rel err {err:.3e}")
     assert err <= out_tol(w)
+
+
+@pytest.mark.parametrize("base,kw,b,tol", [
+    ("cfg1", dict(n=256, d=64, e=8, c=2.0, d_ff=128, act=wl.ACT_GELU), 1.0, 1e-5),   # fp32
+    ("cfg2", dict(n=2048, d=512, e=16, d_ff=1024), 2.0, 2e-2),                       # bf16, matrix-core path
+])
+def test_capped_backward(m, ref, base, kw, b, tol):
+    # The capped variant changes only where I comes from (TopK of A instead of TopK of S); G stays S at the chosen
+    # indices, so the backward pass of Eq. 2-4 applies unchanged: ec_moe_backward on the capped routing against the
+    # oracle's backward on the same routing.
+    w = sized(wl.WORKLOADS[base], backward=True, **kw)
+    inp = wl.make_inputs(w)
+    n, d, e, f = w.n, w.d, w.e, w.d_ff
+    k = ref.capacity(n, w.c, e)
+    lam, iters = 1e-3, 50
+    _p(f"[capped backward] {base} n={n} d={d} e={e} k={k} b={b}")
+    dt = torch_dtype(w)
+    nbytes = m.ec_moe_workspace_bytes(n, d, e, k, f, w.dtype, True) + m.ec_moe_capped_workspace_bytes(n, e) \
+        + (4 * e * n + 255) // 256 * 256
+    ws = torch.empty(nbytes, dtype=torch.uint8, device="cuda")
+    t = {key: to_dev(inp[key]) for key in ("X", "Wg", "W1", "W2", "dY")}
+    dev = dict(device="cuda")
+    f32 = torch.float32
+    Xout = torch.empty((n, d), dtype=dt, **dev)
+    S = torch.empty((n, e), dtype=f32, **dev)
+    G = torch.empty((e, k), dtype=f32, **dev)
+    I = torch.empty((e, k), dtype=torch.int32, **dev)
+    m.ec_moe_forward_capped(t["X"], t["Wg"], t["W1"], t["W2"], w.c, b, lam, iters, Xout, w.act, ws, S_out=S, G_out=G, I_out=I)
+    # the tensors the backward consumes, from the stage-wise entry points on the capped routing
+    Xin = torch.empty((e, k, d), dtype=dt, **dev)
+    A = torch.empty((e, k, f), dtype=dt, **dev)
+    H = torch.empty((e, k, f), dtype=dt, **dev)
+    Xe = torch.empty((e, k, d), dtype=dt, **dev)
+    m.ec_moe_dispatch(t["X"], I, Xin)
+    m.ec_moe_expert_ffn(Xin, t["W1"], t["W2"], Xe, w.act, ws, A_save=A, H_save=H)
+    dX = torch.full((n, d), float("nan"), dtype=dt, **dev)
+    dWg = torch.full((d, e), float("nan"), dtype=f32, **dev)
+    dW1 = torch.full((e, d, f), float("nan"), dtype=f32, **dev)
+    dW2 = torch.full((e, f, d), float("nan"), dtype=f32, **dev)
+    m.ec_moe_backward(t["dY"], t["X"], t["Wg"], t["W1"], t["W2"], S, G, I, Xin, A, H, Xe, dX, dWg, dW1, dW2, w.act, ws)
+    torch.cuda.synchronize()
+    S_h, G_h, I_h = to_host(S), to_host(G), to_host(I)
+    per_token = np.bincount(I_h.ravel(), minlength=n)
+    plain = np.bincount(ref.topk_tokens(S_h, k)[1].ravel(), minlength=n)
+    assert (per_token != plain).any()            # the cap did change the routing this backward runs on
+    g = ref.backward(inp["X"], inp["Wg"], inp["W1"], inp["W2"], w.act, S_h, G_h, I_h, inp["dY"])
+    for key, got in (("dX", dX), ("dWg", dWg), ("dW1", dW1), ("dW2", dW2)):
+        err = max_rel_err(to_host(got), g[key])
+        _p(f"[capped backward] {key} max rel err {err:.3e}")
+        assert err <= tol
