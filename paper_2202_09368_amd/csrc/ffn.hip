@@ -268,18 +268,17 @@ static int gemm_bf16_dispatch(const bf16_t* A, const bf16_t* B, bf16_t* C, bf16_
     const double c4 = cost(256, 192, 1, 0.95);  // fills the chip exactly when 256 x 256 tiles leave units idle
     int pick = (c0 <= c1 && c0 <= c2) ? 0 : (c1 <= c2 ? 1 : 2);
     if (c4 < c0 && c4 < c1 && c4 < c2) pick = 4;
-    // Short contractions leave the epilogue (activation, stores) as large as the MFMA phase: two
-    // co-resident 256 x 128 workgroups per compute unit overlap one's epilogue with the other's MFMAs.
-    if (pick == 0 && K <= 1024 && cost(256, 128, 2, 1.0) <= 1.25 * c0) pick = 3;
-    // still shorter contractions: 128 x 128 tiles, twice as many workgroups in flight (measured on
-    // K = 768: 98-102 us against 104-110 us for the 256 x 128 pairs)
-    if (pick == 3 && K <= 768 && cost(128, 128, 2, 1.0) <= 1.25 * c0) pick = 2;
+    // Short contractions leave the epilogue (activation, stores) as large as the MFMA phase: 128 x 128 tiles, two
+    // workgroups per compute unit, overlap one's epilogue with the other's MFMAs.  Measured with the GeLU epilogue:
+    // K = 768 (16 x 1024 x 3072): 103 us against 105 (256 x 256) and 111 (256 x 128 pairs); from K = 1024 on
+    // (64 x 512 x 4096) the 256 x 256 tile wins, 344 us against 356 and 369.
+    if (pick == 0 && K <= 768 && cost(128, 128, 2, 1.0) <= 1.25 * c0) pick = 2;
     switch (pick) {
         case 0: return launch_gemm_bf16<256, 256, 2, 1>(A, B, C, Cpre, G, M, N, K, act, gather, gather_rows, stream);
         case 1: return launch_gemm_bf16<256, 128, 2, 1>(A, B, C, Cpre, G, M, N, K, act, gather, gather_rows, stream);
         case 2: return launch_gemm_bf16<128, 128, 1, 2>(A, B, C, Cpre, G, M, N, K, act, gather, gather_rows, stream);
         case 4: return launch_gemm_bf16<256, 192, 2, 1>(A, B, C, Cpre, G, M, N, K, act, gather, gather_rows, stream);
-        default: return launch_gemm_bf16<256, 128, 1, 2>(A, B, C, Cpre, G, M, N, K, act, gather, gather_rows, stream);
+        default: return launch_gemm_bf16<256, 256, 2, 1>(A, B, C, Cpre, G, M, N, K, act, gather, gather_rows, stream);
     }
 }
 
@@ -352,8 +351,12 @@ static int launch_gemm_f32(const float* A, const float* B, float* C, float* Cpre
 // Xe = act(Xin.W1).W2 ; H is the [e,k,d_ff] hidden buffer (workspace or caller's).
 // ---------------------------------------------------------------------------
 // True when the first product can gather its rows straight from X (no X_in buffer needed).
+// It is used only while X is small (16 MiB: it then stays in the L2 caches): the tile loader reads every bucket row
+// once per column of tiles, and rows scattered over a large X cost more there than one pass of the dispatch kernel
+// (measured: 8192 x 768 tokens, gathered product 99 us against 103 + 13 for the dispatch; 16384 x 1024 tokens,
+// 383 us against 344 + 25).
 bool ffn_can_gather(int dtype, int64_t n, int64_t k, int64_t d, int64_t d_ff) {
-    return dtype == EC_BF16 && k > 0 && gemm_bf16_fast_ok(k, d_ff, d, true, n);
+    return dtype == EC_BF16 && k > 0 && n * d * 2 <= ((int64_t)16 << 20) && gemm_bf16_fast_ok(k, d_ff, d, true, n);
 }
 
 

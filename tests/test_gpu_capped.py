@@ -118,7 +118,7 @@ def test_capped_forward(m, ref, base, kw, b, iters):
 
 @pytest.mark.parametrize("base,kw,b,tol", [
     ("cfg1", dict(n=256, d=64, e=8, c=2.0, d_ff=128, act=wl.ACT_GELU), 1.0, 1e-5),   # fp32
-    ("cfg2", dict(n=2048, d=512, e=16, d_ff=1024), 2.0, 2e-2),                       # bf16, matrix-core path
+    ("cfg2", dict(n=4096, d=256, e=8, d_ff=512), 2.0, 2e-2),                         # bf16, matrix-core path, k = 1024
 ])
 def test_capped_backward(m, ref, base, kw, b, tol):
     # The capped variant changes only where I comes from (TopK of A instead of TopK of S); G stays S at the chosen
