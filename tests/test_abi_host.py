@@ -118,4 +118,14 @@ def test_invalid_arguments_are_rejected_on_the_host(m):
     assert cap(2.0, 1e-3, -1, P, 1 << 30) == INV
     assert cap(2.0, 1e-3, 10, P, 64) == WS
     assert m.ec_moe_capped_workspace_bytes(0, 4) == 0 and m.ec_moe_capped_workspace_bytes(64, 4) >= 2 * 64 * 4 * 8
+    # the combine without a workspace: same argument checks (its size limit needs a GPU: the array's address is looked up first)
+    assert lib.ec_moe_combine_static(P, P, None, P, 8, 16, 2, 4, 1, None) == INV
+    assert lib.ec_moe_combine_static(P, P, P, P, 8, 12, 2, 4, 1, None) == INV
+    # the timed backward: a host pointer for the stage times is required; stage names
+    bwd_args = [P] * 16 + [64, 16, 4, 32, 32, 1, 1, P, 1 << 40, None]
+    assert lib.ec_moe_backward_timed(*bwd_args, None) == INV
+    assert lib.ec_moe_backward(*([None] + bwd_args[1:])) == INV
+    assert lib.ec_moe_backward(*(bwd_args[:-3] + [P, 64, None])) == WS
+    assert lib.ec_moe_backward_stage_name(0) == b"bwd_rows" and lib.ec_moe_backward_stage_name(8) == b"bwd_scatter"
+    assert lib.ec_moe_backward_stage_name(9) is None and lib.ec_moe_backward_stage_name(-1) is None
     assert m.ec_moe_last_hip_error() == 0      # nothing was launched
