@@ -468,6 +468,29 @@ gemm_bf16_kernel(const bf16_t* __restrict__ Aall, const bf16_t* __restrict__ Bal
         }
     } else {
         float* strip = reinterpret_cast<float*>(smem_raw) + wave * 32 * EPI_STRIDE;
+        // EPI_MULGRAD: the pre-activations and row weights this lane will need are requested for the whole wave tile
+        // up front (the staging registers of the main loop are free now), so the strips below wait for memory once.
+        constexpr int MG_CHUNKS_PER_ROW = WN / 8, MG_ROWS_PER_PASS = 64 / MG_CHUNKS_PER_ROW;
+        constexpr int MG_PASSES = EPI == EPI_MULGRAD ? 32 / MG_ROWS_PER_PASS : 1;
+        bf16x8 mg_aux[EPI == EPI_MULGRAD ? TM : 1][MG_PASSES];
+        float mg_rs[EPI == EPI_MULGRAD ? TM : 1][MG_PASSES];
+        if (EPI == EPI_MULGRAD) {
+            const bf16_t* __restrict__ Aux = reinterpret_cast<const bf16_t*>(C2all) + gofs;
+            const int er = lane / MG_CHUNKS_PER_ROW, ec = lane % MG_CHUNKS_PER_ROW;
+#pragma unroll
+            for (int i = 0; i < TM; ++i)
+#pragma unroll
+                for (int p = 0; p < MG_PASSES; ++p) {
+                    const int row = p * MG_ROWS_PER_PASS + er;
+                    const int gm = m0 + wr * WM + i * 32 + row;
+                    const int gn = n0 + wc * WN + ec * 8;
+                    const bool in = er < MG_ROWS_PER_PASS && row < 32 && gm < M && gn < N;
+                    bf16x8 a = {};
+                    if (in) a = *reinterpret_cast<const bf16x8*>(Aux + (size_t)gm * N + gn);
+                    mg_aux[i][p] = a;
+                    mg_rs[i][p] = (in && row_scale != nullptr) ? row_scale[(size_t)g * M + gm] : 1.0f;
+                }
+        }
 #pragma unroll
         for (int i = 0; i < TM; ++i) {
 #pragma unroll
@@ -496,9 +519,8 @@ gemm_bf16_kernel(const bf16_t* __restrict__ Aall, const bf16_t* __restrict__ Bal
             } else {
                 bf16_t* __restrict__ C = reinterpret_cast<bf16_t*>(Call) + gofs;
                 bf16_t* __restrict__ Clo = C3all != nullptr ? reinterpret_cast<bf16_t*>(C3all) + gofs : nullptr;
-                const bf16_t* __restrict__ Aux = reinterpret_cast<const bf16_t*>(C2all) + gofs;
-                constexpr int CHUNKS_PER_ROW = WN / 8;
-                constexpr int ROWS_PER_PASS = 64 / CHUNKS_PER_ROW;
+                constexpr int CHUNKS_PER_ROW = MG_CHUNKS_PER_ROW;
+                constexpr int ROWS_PER_PASS = MG_ROWS_PER_PASS;
                 const int er = lane / CHUNKS_PER_ROW, ec = lane % CHUNKS_PER_ROW;
 #pragma unroll
                 for (int rr = 0; rr < 32; rr += ROWS_PER_PASS) {
@@ -508,8 +530,8 @@ gemm_bf16_kernel(const bf16_t* __restrict__ Aall, const bf16_t* __restrict__ Bal
                     if (er < ROWS_PER_PASS && row < 32 && gm < M && gn < N) {
                         const floatx4 v0 = *reinterpret_cast<const floatx4*>(&strip[row * EPI_STRIDE + ec * 8]);
                         const floatx4 v1 = *reinterpret_cast<const floatx4*>(&strip[row * EPI_STRIDE + ec * 8 + 4]);
-                        const bf16x8 a = *reinterpret_cast<const bf16x8*>(Aux + (size_t)gm * N + gn);
-                        const float rs = row_scale != nullptr ? row_scale[(size_t)g * M + gm] : 1.0f;
+                        const bf16x8 a = mg_aux[EPI == EPI_MULGRAD ? i : 0][EPI == EPI_MULGRAD ? rr / ROWS_PER_PASS : 0];
+                        const float rs = mg_rs[EPI == EPI_MULGRAD ? i : 0][EPI == EPI_MULGRAD ? rr / ROWS_PER_PASS : 0];
                         bf16x8 o, lo;
 #pragma unroll
                         for (int t = 0; t < 4; ++t) {
