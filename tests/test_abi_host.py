@@ -129,3 +129,17 @@ def test_invalid_arguments_are_rejected_on_the_host(m):
     assert lib.ec_moe_backward_stage_name(0) == b"bwd_rows" and lib.ec_moe_backward_stage_name(8) == b"bwd_scatter"
     assert lib.ec_moe_backward_stage_name(9) is None and lib.ec_moe_backward_stage_name(-1) is None
     assert m.ec_moe_last_hip_error() == 0      # nothing was launched
+
+
+def test_the_header_is_plain_c(tmp_path):
+    # the boundary is a C ABI: the header must compile as C99 on its own (no C++ constructs, no torch types)
+    import shutil
+    import subprocess
+    gcc = shutil.which("gcc")
+    if gcc is None:
+        pytest.skip("no C compiler")
+    src = tmp_path / "use_header.c"
+    src.write_text('#include "ec_moe.h"\nint main(void) { long long k = 0; return ec_moe_capacity(8, 2, 1.0, (int64_t*)&k); }\n')
+    r = subprocess.run([gcc, "-std=c99", "-Wall", "-Wextra", "-pedantic", "-Werror", "-fsyntax-only",
+                        "-I", os.path.join(ROOT, "include"), str(src)], capture_output=True, text=True)
+    assert r.returncode == 0, r.stderr
