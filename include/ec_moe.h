@@ -136,7 +136,8 @@ int ec_moe_combine(const void* Xe, const float* G, const int32_t* I, void* Xout,
  * (the smallest that holds e); e > 16: 4*n*ceil(e/32) + 4*(n+1) + 4*e*k + 4096 bytes, each part rounded up
  * to 256.  Larger problems return EC_ERR_UNSUPPORTED and enqueue nothing.
  * All calls on one GPU share the array, which keeps the previous call's contents: calls that overlap
- * on one GPU (different streams, or threads without ordering) race; order them on one stream. */
+ * on one GPU (different streams, or threads without ordering) race; order them on one stream.
+ * The array's device address is looked up at the first call on a GPU: make that call outside a capture. */
 #define EC_MOE_STATIC_SCRATCH_BYTES (8u << 20)
 int ec_moe_combine_static(const void* Xe, const float* G, const int32_t* I, void* Xout,
                           int64_t n, int64_t d, int64_t e, int64_t k, int dtype, void* stream);

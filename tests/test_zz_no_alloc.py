@@ -65,3 +65,30 @@ def test_static_scratch_combine_refuses_what_does_not_fit():
     with pytest.raises(m.EcMoeError) as ei:
         m.ec_moe_combine_static(Xe, G, I, out)
     assert ei.value.status == -4
+
+
+def test_static_scratch_combine_under_graph_capture():
+    # what the entry point is for: a caller that captures the call in a HIP graph.  The array's address is looked up
+    # at the first call on a device, so one call is made before the capture; every replay, with eager work and
+    # synchronisations in between, must equal the eager result (the index is cleared by a kernel, not a memset node).
+    n, e, k, d = 4096, 64, 128, 256
+    Xe, G, I = _routing(n, e, k, d, True, 7)
+    out = torch.empty((n, d), dtype=torch.bfloat16, device="cuda")
+    m.ec_moe_combine_static(Xe, G, I, out)
+    torch.cuda.synchronize()
+    eager = to_host(out)
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        m.ec_moe_combine_static(Xe, G, I, out)
+    torch.cuda.current_stream().wait_stream(side)
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        m.ec_moe_combine_static(Xe, G, I, out)
+    torch.cuda.synchronize()
+    for _ in range(3):
+        out.fill_(1.0)
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        assert (to_host(out) == eager).all()
