@@ -48,7 +48,16 @@ typedef enum {
     EC_ERR_UNSUPPORTED = -4  /* valid request outside what the kernels cover */
 } ec_status;
 
-typedef enum { EC_F32 = 0, EC_BF16 = 1 } ec_dtype;
+/* EC_BF16_HILO: storage and interface exactly as EC_BF16; the two intermediates that EC_BF16 hands to a
+ * matrix-core product as single bf16 numbers -- H = act(A) into the second product of Eq. 3, and dX_e = G dY into
+ * dW2 -- are carried as high part + remainder (two bf16 numbers, 2^-17), and X_e goes into the sum of Eq. 4
+ * unrounded.  Those two products do twice the work.  It is for callers who need every element of large outputs
+ * within 2e-2 of an unrounded reference: with EC_BF16 a token's output row scales with its gate values while that
+ * error measure is relative to the whole tensor, and the worst element of tens of millions reaches 2-3e-2.
+ * Honoured by ec_moe_expert_ffn, ec_moe_forward, ec_moe_forward_grouped, ec_moe_backward(_timed) and
+ * ec_moe_workspace_bytes (d and d_ff multiples of 64, else EC_ERR_UNSUPPORTED); the routing and data-movement
+ * entry points treat it as EC_BF16; the token-choice and capped layers return EC_ERR_UNSUPPORTED. */
+typedef enum { EC_F32 = 0, EC_BF16 = 1, EC_BF16_HILO = 2 } ec_dtype;
 typedef enum { EC_ACT_RELU = 0, EC_ACT_GELU = 1 /* exact erf form */, EC_ACT_IDENTITY = 2 } ec_act;
 
 /* Largest number of experts the routing kernels accept. */
@@ -60,7 +69,8 @@ int ec_moe_capacity(int64_t n, int64_t e, double c, int64_t* k);
 
 /* Host only.  Bytes of workspace sufficient for ANY entry point below at these
  * sizes (d_ff may be 0 for identity experts; with_backward != 0 adds what
- * ec_moe_backward needs).  Returns 0 for invalid sizes. */
+ * ec_moe_backward needs).  Returns 0 for invalid sizes, and for EC_BF16_HILO with
+ * an FFN whose widths that mode does not cover. */
 size_t ec_moe_workspace_bytes(int64_t n, int64_t d, int64_t e, int64_t k, int64_t d_ff,
                               int dtype, int with_backward);
 

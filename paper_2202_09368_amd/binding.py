@@ -14,7 +14,7 @@ from typing import Optional
 
 import torch
 
-EC_F32, EC_BF16 = 0, 1
+EC_F32, EC_BF16, EC_BF16_HILO = 0, 1, 2
 EC_ACT_RELU, EC_ACT_GELU, EC_ACT_IDENTITY = 0, 1, 2
 EC_MOE_MAX_EXPERTS = 1024
 
@@ -84,11 +84,14 @@ def lib() -> ctypes.CDLL:
 
 
 # ------------------------------------------------------------------ helpers --
-def _dtype_code(t: torch.Tensor) -> int:
+def _dtype_code(t: torch.Tensor, hilo: bool = False) -> int:
+    """ec_dtype of a tensor; hilo asks for EC_BF16_HILO (bf16 storage, two-part matrix-core operands)."""
     if t.dtype == torch.float32:
+        if hilo:
+            raise TypeError("hilo applies to bf16 storage")
         return EC_F32
     if t.dtype == torch.bfloat16:
-        return EC_BF16
+        return EC_BF16_HILO if hilo else EC_BF16
     raise TypeError(f"unsupported storage type {t.dtype}")
 
 
@@ -160,14 +163,14 @@ def ec_moe_dispatch(X, I, Xin) -> None:
                                                     _dtype_code(X), _stream()))
 
 
-def ec_moe_expert_ffn(Xin, W1, W2, Xe, act: int, ws, A_save=None, H_save=None) -> None:
+def ec_moe_expert_ffn(Xin, W1, W2, Xe, act: int, ws, A_save=None, H_save=None, hilo: bool = False) -> None:
     e, k, d = Xin.shape
     d_ff = W1.shape[2]
     wp, wb = _ws(ws)
     dt = Xin.dtype
     _check("ec_moe_expert_ffn", lib().ec_moe_expert_ffn(_ptr(Xin), _ptr(W1, dt), _ptr(W2, dt), _ptr(Xe, dt),
                                                         _ptr(A_save, dt), _ptr(H_save, dt), e, k, d, d_ff, act,
-                                                        _dtype_code(Xin), wp, wb, _stream()))
+                                                        _dtype_code(Xin, hilo), wp, wb, _stream()))
 
 
 def ec_moe_combine(Xe, G, I, Xout, ws) -> None:
@@ -188,7 +191,7 @@ def ec_moe_combine_static(Xe, G, I, Xout) -> None:
 
 
 def ec_moe_forward(X, Wg, W1, W2, c: float, Xout, act: int, ws, S_out=None, G_out=None, I_out=None,
-                   Xin_out=None, A_out=None, H_out=None, Xe_out=None) -> None:
+                   Xin_out=None, A_out=None, H_out=None, Xe_out=None, hilo: bool = False) -> None:
     n, d = X.shape
     e = Wg.shape[1]
     d_ff = W1.shape[2] if W1 is not None else 0
@@ -197,7 +200,7 @@ def ec_moe_forward(X, Wg, W1, W2, c: float, Xout, act: int, ws, S_out=None, G_ou
     _check("ec_moe_forward", lib().ec_moe_forward(
         _ptr(X), _ptr(Wg, dt), _ptr(W1, dt), _ptr(W2, dt), c, _ptr(Xout, dt), _ptr(S_out, torch.float32),
         _ptr(G_out, torch.float32), _ptr(I_out, torch.int32), _ptr(Xin_out, dt), _ptr(A_out, dt), _ptr(H_out, dt),
-        _ptr(Xe_out, dt), n, d, e, d_ff, act, _dtype_code(X), wp, wb, _stream()))
+        _ptr(Xe_out, dt), n, d, e, d_ff, act, _dtype_code(X, hilo), wp, wb, _stream()))
 
 
 def ec_moe_topk_tokens_grouped(St, groups: int, k_g: int, G, I, ws=None) -> None:
@@ -208,7 +211,7 @@ def ec_moe_topk_tokens_grouped(St, groups: int, k_g: int, G, I, ws=None) -> None
 
 
 def ec_moe_forward_grouped(X, Wg, W1, W2, c: float, groups: int, Xout, act: int, ws, S_out=None, G_out=None,
-                           I_out=None, Xin_out=None, A_out=None, H_out=None, Xe_out=None) -> None:
+                           I_out=None, Xin_out=None, A_out=None, H_out=None, Xe_out=None, hilo: bool = False) -> None:
     n, d = X.shape
     e = Wg.shape[1]
     d_ff = W1.shape[2] if W1 is not None else 0
@@ -217,7 +220,7 @@ def ec_moe_forward_grouped(X, Wg, W1, W2, c: float, groups: int, Xout, act: int,
     _check("ec_moe_forward_grouped", lib().ec_moe_forward_grouped(
         _ptr(X), _ptr(Wg, dt), _ptr(W1, dt), _ptr(W2, dt), c, groups, _ptr(Xout, dt), _ptr(S_out, torch.float32),
         _ptr(G_out, torch.float32), _ptr(I_out, torch.int32), _ptr(Xin_out, dt), _ptr(A_out, dt), _ptr(H_out, dt),
-        _ptr(Xe_out, dt), n, d, e, d_ff, act, _dtype_code(X), wp, wb, _stream()))
+        _ptr(Xe_out, dt), n, d, e, d_ff, act, _dtype_code(X, hilo), wp, wb, _stream()))
 
 
 def ec_moe_token_choice(S, m: int, cap: int, G, I, load, ws) -> None:
@@ -265,7 +268,7 @@ def ec_moe_forward_capped(X, Wg, W1, W2, c: float, b: float, lam: float, iters: 
         _ptr(Xe_out, dt), n, d, e, d_ff, act, _dtype_code(X), wp, wb, _stream()))
 
 
-def ec_moe_backward(dY, X, Wg, W1, W2, S, G, I, Xin, A, H, Xe, dX, dWg, dW1, dW2, act: int, ws) -> None:
+def ec_moe_backward(dY, X, Wg, W1, W2, S, G, I, Xin, A, H, Xe, dX, dWg, dW1, dW2, act: int, ws, hilo: bool = False) -> None:
     n, d = X.shape
     e, k = I.shape
     d_ff = W1.shape[2]
@@ -275,13 +278,14 @@ def ec_moe_backward(dY, X, Wg, W1, W2, S, G, I, Xin, A, H, Xe, dX, dWg, dW1, dW2
     _check("ec_moe_backward", lib().ec_moe_backward(
         _ptr(dY, dt), _ptr(X), _ptr(Wg, dt), _ptr(W1, dt), _ptr(W2, dt), _ptr(S, f32), _ptr(G, f32),
         _ptr(I, torch.int32), _ptr(Xin, dt), _ptr(A, dt), _ptr(H, dt), _ptr(Xe, dt), _ptr(dX, dt), _ptr(dWg, f32),
-        _ptr(dW1, f32), _ptr(dW2, f32), n, d, e, k, d_ff, act, _dtype_code(X), wp, wb, _stream()))
+        _ptr(dW1, f32), _ptr(dW2, f32), n, d, e, k, d_ff, act, _dtype_code(X, hilo), wp, wb, _stream()))
 
 
 EC_MOE_BWD_STAGES = 9
 
 
-def ec_moe_backward_timed(dY, X, Wg, W1, W2, S, G, I, Xin, A, H, Xe, dX, dWg, dW1, dW2, act: int, ws) -> dict:
+def ec_moe_backward_timed(dY, X, Wg, W1, W2, S, G, I, Xin, A, H, Xe, dX, dWg, dW1, dW2, act: int, ws,
+                          hilo: bool = False) -> dict:
     """ec_moe_backward with HIP events between its stages; waits, returns {stage name: milliseconds}."""
     n, d = X.shape
     e, k = I.shape
@@ -293,7 +297,7 @@ def ec_moe_backward_timed(dY, X, Wg, W1, W2, S, G, I, Xin, A, H, Xe, dX, dWg, dW
     _check("ec_moe_backward_timed", lib().ec_moe_backward_timed(
         _ptr(dY, dt), _ptr(X), _ptr(Wg, dt), _ptr(W1, dt), _ptr(W2, dt), _ptr(S, f32), _ptr(G, f32),
         _ptr(I, torch.int32), _ptr(Xin, dt), _ptr(A, dt), _ptr(H, dt), _ptr(Xe, dt), _ptr(dX, dt), _ptr(dWg, f32),
-        _ptr(dW1, f32), _ptr(dW2, f32), n, d, e, k, d_ff, act, _dtype_code(X), wp, wb, _stream(), ms))
+        _ptr(dW1, f32), _ptr(dW2, f32), n, d, e, k, d_ff, act, _dtype_code(X, hilo), wp, wb, _stream(), ms))
     return {lib().ec_moe_backward_stage_name(i).decode(): float(ms[i]) for i in range(EC_MOE_BWD_STAGES)}
 
 

@@ -12,6 +12,8 @@ void set_last_hip_error(hipError_t err) { g_last_hip_error = (int)err; }
 
 WsLayout ws_layout(int64_t n, int64_t d, int64_t e, int64_t k, int64_t d_ff, int dtype, int with_backward) {
     WsLayout L;
+    const bool hilo = dtype == EC_BF16_HILO && d_ff > 0;  // identity experts: no product, nothing to carry in two parts
+    if (dtype == EC_BF16_HILO) dtype = EC_BF16;
     const size_t es = elem_size(dtype);
     size_t off = 0;
     auto take = [&](size_t bytes) {
@@ -25,6 +27,8 @@ WsLayout ws_layout(int64_t n, int64_t d, int64_t e, int64_t k, int64_t d_ff, int
     L.xin = take((size_t)e * k * d * es);
     L.h = take((size_t)e * k * (size_t)(d_ff > 0 ? d_ff : 0) * es);
     L.xe = take((size_t)e * k * d * es);
+    L.h_lo = take(hilo ? (size_t)e * k * (size_t)(d_ff > 0 ? d_ff : 0) * 2 : 0);
+    L.xe32 = take(hilo ? (size_t)e * k * d * 4 : 0);
     L.bitmap = take((size_t)n * (size_t)ceil_div(e, 32) * 4);
     L.offsets = take((size_t)(n + 1) * 4);
     L.inv = take((size_t)e * k * 4);
@@ -32,7 +36,7 @@ WsLayout ws_layout(int64_t n, int64_t d, int64_t e, int64_t k, int64_t d_ff, int
     L.slots = take((size_t)n * COMBINE_SLOT_CAP * 4);
     L.choice = take((size_t)n * 8 * 4);
     L.bwd = off;
-    if (with_backward) take(bwd_ws_bytes(n, d, e, k, d_ff, dtype));
+    if (with_backward) take(bwd_ws_bytes(n, d, e, k, d_ff, dtype, hilo));
     L.total = off;
     return L;
 }
@@ -41,9 +45,14 @@ static bool sizes_ok(int64_t n, int64_t d, int64_t e, int64_t k) {
     return n > 0 && d > 0 && e > 0 && k >= 1 && k <= n && n < (int64_t)1 << 31 && d < (int64_t)1 << 31 &&
            e <= EC_MOE_MAX_EXPERTS && e * k < (int64_t)1 << 31;
 }
-static bool dtype_ok(int dtype) { return dtype == EC_F32 || dtype == EC_BF16; }
+static bool dtype_ok(int dtype) { return dtype == EC_F32 || dtype == EC_BF16 || dtype == EC_BF16_HILO; }
+// EC_BF16_HILO stores what EC_BF16 stores; `*hilo` says whether the two-part operands were asked for.
+static int storage_dtype(int dtype, bool* hilo = nullptr) {
+    if (hilo != nullptr) *hilo = dtype == EC_BF16_HILO;
+    return dtype == EC_BF16_HILO ? EC_BF16 : dtype;
+}
 static bool act_ok(int act) { return act == EC_ACT_RELU || act == EC_ACT_GELU || act == EC_ACT_IDENTITY; }
-static bool width_ok(int64_t w, int dtype) { return dtype != EC_BF16 || (w % 8) == 0; }
+static bool width_ok(int64_t w, int dtype) { return dtype == EC_F32 || (w % 8) == 0; }
 template <typename... P>
 static bool all_aligned(P... ptrs) {
     bool ok = true;
@@ -85,6 +94,7 @@ int ec_moe_capacity(int64_t n, int64_t e, double c, int64_t* k) {
 size_t ec_moe_workspace_bytes(int64_t n, int64_t d, int64_t e, int64_t k, int64_t d_ff, int dtype,
                               int with_backward) {
     if (!sizes_ok(n, d, e, k) || d_ff < 0 || !dtype_ok(dtype)) return 0;
+    if (dtype == EC_BF16_HILO && d_ff > 0 && !ffn_can_hilo(EC_BF16, k, d, d_ff)) return 0;  // no such layer: see EC_ERR_UNSUPPORTED
     return ws_layout(n, d, e, k, d_ff, dtype, with_backward).total;
 }
 
@@ -93,6 +103,7 @@ int ec_moe_gate(const void* X, const void* Wg, float* S, float* St, int64_t n, i
     if (!X || !Wg || (!S && !St) || n <= 0 || d <= 0 || e <= 0 || e > EC_MOE_MAX_EXPERTS || n >= (int64_t)1 << 31 ||
         !dtype_ok(dtype) || !all_aligned(X, Wg, S, St))
         return EC_ERR_INVALID_ARG;
+    dtype = storage_dtype(dtype);
     (void)ws; (void)ws_bytes;  // the gate needs no scratch
     return launch_gate(X, Wg, S, St, n, d, e, dtype, nullptr, 0, (hipStream_t)stream);
 }
@@ -119,6 +130,7 @@ int ec_moe_dispatch(const void* X, const int32_t* I, void* Xin, int64_t n, int64
     if (!X || !I || !Xin || !sizes_ok(n, d, e, k) || !dtype_ok(dtype) || !width_ok(d, dtype) ||
         !all_aligned(X, I, Xin))
         return EC_ERR_INVALID_ARG;
+    dtype = storage_dtype(dtype);
     return launch_dispatch(X, I, Xin, n, d, e, k, dtype, (hipStream_t)stream);
 }
 
@@ -130,13 +142,19 @@ int ec_moe_expert_ffn(const void* Xin, const void* W1, const void* W2, void* Xe,
         !act_ok(act) || !width_ok(d, dtype) || !width_ok(d_ff, dtype) ||
         !all_aligned(Xin, W1, W2, Xe, A_save, H_save))
         return EC_ERR_INVALID_ARG;
-    void* H = H_save;
-    if (!H) {
-        const size_t need = align_up((size_t)e * k * d_ff * elem_size(dtype), 256);
-        if (!ws_ok(ws, ws_bytes, need)) return EC_ERR_WORKSPACE;
-        H = ws;
-    }
-    return launch_ffn(Xin, nullptr, nullptr, 0, W1, W2, Xe, A_save, H, e, k, d, d_ff, act, dtype, (hipStream_t)stream);
+    bool hilo = false;
+    dtype = storage_dtype(dtype, &hilo);
+    if (hilo && !ffn_can_hilo(dtype, k, d, d_ff)) return EC_ERR_UNSUPPORTED;
+    // workspace: H unless the caller keeps it; with two-part operands the remainder of H and X_e unrounded
+    const size_t h_bytes = H_save ? 0 : align_up((size_t)e * k * d_ff * elem_size(dtype), 256);
+    const size_t hlo_bytes = hilo ? align_up((size_t)e * k * d_ff * 2, 256) : 0;
+    const size_t xe32_bytes = hilo ? align_up((size_t)e * k * d * 4, 256) : 0;
+    if (!ws_ok(ws, ws_bytes, h_bytes + hlo_bytes + xe32_bytes)) return EC_ERR_WORKSPACE;
+    void* H = H_save ? H_save : ws;
+    void* H_lo = hilo ? at(ws, h_bytes) : nullptr;
+    float* Xe32 = hilo ? (float*)at(ws, h_bytes + hlo_bytes) : nullptr;
+    return launch_ffn(Xin, nullptr, nullptr, 0, W1, W2, Xe, A_save, H, e, k, d, d_ff, act, dtype, (hipStream_t)stream, H_lo,
+                      Xe32);
 }
 
 int ec_moe_combine(const void* Xe, const float* G, const int32_t* I, void* Xout, int64_t n, int64_t d, int64_t e,
@@ -144,6 +162,7 @@ int ec_moe_combine(const void* Xe, const float* G, const int32_t* I, void* Xout,
     if (!Xe || !G || !I || !Xout || !sizes_ok(n, d, e, k) || !dtype_ok(dtype) || !width_ok(d, dtype) ||
         !all_aligned(Xe, G, I, Xout))
         return EC_ERR_INVALID_ARG;
+    dtype = storage_dtype(dtype);
     // token-major index: carved from the front of the workspace
     WsLayout L;
     size_t off = 0;
@@ -165,6 +184,7 @@ int ec_moe_combine_static(const void* Xe, const float* G, const int32_t* I, void
     if (!Xe || !G || !I || !Xout || !sizes_ok(n, d, e, k) || !dtype_ok(dtype) || !width_ok(d, dtype) ||
         !all_aligned(Xe, G, I, Xout))
         return EC_ERR_INVALID_ARG;
+    dtype = storage_dtype(dtype);
     return combine_static(Xe, G, I, Xout, n, d, e, k, dtype, (hipStream_t)stream);
 }
 
@@ -190,6 +210,10 @@ static int forward_impl(const void* X, const void* Wg, const void* W1, const voi
     }
     const WsLayout L = ws_layout(n, d, e, k, d_ff, dtype, 0);
     if (!ws_ok(ws, ws_bytes, L.total)) return EC_ERR_WORKSPACE;
+    bool hilo = false;
+    dtype = storage_dtype(dtype, &hilo);
+    if (identity) hilo = false;  // no product, nothing to carry in two parts
+    if (hilo && !ffn_can_hilo(dtype, k, d, d_ff)) return EC_ERR_UNSUPPORTED;
     hipStream_t st = (hipStream_t)stream;
 
     float* St = (float*)at(ws, L.st);
@@ -223,6 +247,15 @@ static int forward_impl(const void* X, const void* Wg, const void* W1, const voi
         if (rc != EC_OK) return rc;
     }
     void* H = H_out ? H_out : at(ws, L.h);
+    if (hilo) {
+        // H leaves the first product as high part + remainder, X_e reaches the sum of Eq. 4 unrounded (the bf16 X_e
+        // is written only for a caller who asks for it)
+        float* Xe32 = (float*)at(ws, L.xe32);
+        rc = launch_ffn(fused_gather ? nullptr : Xin, X, I, n, W1, W2, Xe_out, A_out, H, e, k, d, d_ff, act, dtype, st,
+                        at(ws, L.h_lo), Xe32);
+        if (rc != EC_OK) return rc;
+        return launch_combine(Xe32, G, I, Xout, n, d, e, k, dtype, ix, st, nullptr, false, nullptr, true);
+    }
     void* Xe = Xe_out ? Xe_out : at(ws, L.xe);
     rc = launch_ffn(fused_gather ? nullptr : Xin, X, I, n, W1, W2, Xe, A_out, H, e, k, d, d_ff, act, dtype, st);
     if (rc != EC_OK) return rc;
@@ -261,6 +294,7 @@ int ec_moe_forward_token_choice(const void* X, const void* Wg, const void* W1, c
                                 int64_t d_ff, int act, int dtype, void* ws, size_t ws_bytes, void* stream) {
     int64_t k = 0;  // rows of an expert's buffer
     if (ec_moe_capacity(n, e, c, &k) != EC_OK || m < 1 || m > e || m > 8) return EC_ERR_INVALID_ARG;
+    if (dtype == EC_BF16_HILO) return EC_ERR_UNSUPPORTED;
     const bool identity = (W1 == nullptr && W2 == nullptr);
     if (!X || !Wg || !Xout || !sizes_ok(n, d, e, k) || !dtype_ok(dtype) || !act_ok(act) || !width_ok(d, dtype) ||
         !all_aligned(X, Wg, W1, W2, Xout, S_out, G_out, I_out, load_out, Xin_out, A_out, H_out, Xe_out))
@@ -327,6 +361,7 @@ int ec_moe_forward_capped(const void* X, const void* Wg, const void* W1, const v
                           int dtype, void* ws, size_t ws_bytes, void* stream) {
     int64_t k = 0;
     if (ec_moe_capacity(n, e, c, &k) != EC_OK || !capped_args_ok(b, lambda, iters)) return EC_ERR_INVALID_ARG;
+    if (dtype == EC_BF16_HILO) return EC_ERR_UNSUPPORTED;
     const bool identity = (W1 == nullptr && W2 == nullptr);
     if (!X || !Wg || !Xout || !sizes_ok(n, d, e, k) || !dtype_ok(dtype) || !act_ok(act) || !width_ok(d, dtype) ||
         !all_aligned(X, Wg, W1, W2, Xout, S_out, G_out, I_out, A_out, Xe_out))
@@ -389,8 +424,10 @@ int ec_moe_backward(const void* dY, const void* X, const void* Wg, const void* W
         return EC_ERR_INVALID_ARG;
     const WsLayout L = ws_layout(n, d, e, k, d_ff, dtype, 1);
     if (!ws_ok(ws, ws_bytes, L.total)) return EC_ERR_WORKSPACE;
+    bool hilo = false;
+    dtype = storage_dtype(dtype, &hilo);
     return launch_backward(dY, X, Wg, W1, W2, S, G, I, Xin, A, H, Xe, dX, dWg, dW1, dW2, n, d, e, k, d_ff, act,
-                           dtype, ws, L, (hipStream_t)stream);
+                           dtype, ws, L, (hipStream_t)stream, nullptr, hilo);
 }
 
 int ec_moe_backward_timed(const void* dY, const void* X, const void* Wg, const void* W1, const void* W2, const float* S,
@@ -405,6 +442,8 @@ int ec_moe_backward_timed(const void* dY, const void* X, const void* Wg, const v
         return EC_ERR_INVALID_ARG;
     const WsLayout L = ws_layout(n, d, e, k, d_ff, dtype, 1);
     if (!ws_ok(ws, ws_bytes, L.total)) return EC_ERR_WORKSPACE;
+    bool hilo = false;
+    dtype = storage_dtype(dtype, &hilo);
     hipEvent_t marks[BWD_STAGES + 1];
     int made = 0;
     hipError_t err = hipSuccess;
@@ -416,7 +455,7 @@ int ec_moe_backward_timed(const void* dY, const void* X, const void* Wg, const v
         rc = EC_ERR_HIP;
     } else {
         rc = launch_backward(dY, X, Wg, W1, W2, S, G, I, Xin, A, H, Xe, dX, dWg, dW1, dW2, n, d, e, k, d_ff, act, dtype,
-                             ws, L, (hipStream_t)stream, marks);
+                             ws, L, (hipStream_t)stream, marks, hilo);
         if (rc == EC_OK) {
             err = hipEventSynchronize(marks[BWD_STAGES]);
             for (int s = 0; s < BWD_STAGES && err == hipSuccess; ++s)
@@ -452,6 +491,6 @@ const char* ec_moe_status_string(int status) {
     }
 }
 
-const char* ec_moe_version(void) { return "0.1"; }
+const char* ec_moe_version(void) { return "0.2"; }
 
 }  // extern "C"

@@ -20,7 +20,8 @@ namespace ecmoe {
 template <typename T, int VEC, typename TOut>
 __global__ void __launch_bounds__(256)
 bwd_rows_kernel(const T* __restrict__ dY, const T* __restrict__ Xe, const float* __restrict__ G,
-                const int32_t* __restrict__ I, TOut* __restrict__ dXe, float* __restrict__ dG, long long rows, int d) {
+                const int32_t* __restrict__ I, TOut* __restrict__ dXe, float* __restrict__ dG, long long rows, int d,
+                TOut* __restrict__ dXe_lo) {  // dXe_lo (optional): G dY - dXe, what the rounding of dXe dropped
     typedef T vec_t __attribute__((ext_vector_type(VEC)));  // VEC elements = 16 bytes when the rows allow it
     typedef TOut ovec_t __attribute__((ext_vector_type(VEC)));
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
@@ -30,18 +31,21 @@ bwd_rows_kernel(const T* __restrict__ dY, const T* __restrict__ Xe, const float*
         const vec_t* src = reinterpret_cast<const vec_t*>(dY + (size_t)(tok < 0 ? 0 : tok) * d);
         const vec_t* xe = reinterpret_cast<const vec_t*>(Xe + (size_t)r * d);
         ovec_t* dst = reinterpret_cast<ovec_t*>(dXe + (size_t)r * d);
+        ovec_t* dst_lo = dXe_lo != nullptr ? reinterpret_cast<ovec_t*>(dXe_lo + (size_t)r * d) : nullptr;
         const float g = tok < 0 ? 0.0f : G[r];
         float dot = 0.0f;
         for (int t = lane; t < nvec; t += kWave) {
             const vec_t y = src[t], x = xe[t];
-            ovec_t o;
+            ovec_t o, lo;
 #pragma unroll
             for (int q = 0; q < VEC; ++q) {
                 const float yf = Cvt<T>::to_f32(y[q]);
                 dot = fmaf(yf, Cvt<T>::to_f32(x[q]), dot);
                 o[q] = Cvt<TOut>::from_f32(g * yf);
+                lo[q] = Cvt<TOut>::from_f32(g * yf - Cvt<TOut>::to_f32(o[q]));
             }
             dst[t] = o;
+            if (dst_lo != nullptr) dst_lo[t] = lo;
         }
         dot = wave_reduce_sum(dot);
         if (lane == 0) dG[r] = tok < 0 ? 0.0f : dot;
@@ -233,13 +237,13 @@ duplicate_columns_kernel(const bf16_t* __restrict__ Wg, bf16_t* __restrict__ Wg2
 // Workspace of the backward pass (after the forward layout, at L.bwd).
 // ---------------------------------------------------------------------------
 struct BwdLayout {
-    size_t dxe, dg, da, da_lo, dxin, dz, dzb, dxz, wg_part, wg2, total;
+    size_t dxe, dxe_lo, dg, da, da_lo, dxin, dz, dzb, dxz, wg_part, wg2, total;
     int splits;
     int64_t split_len;
     bool mfma;  // the four expert products run on the matrix cores
 };
 
-static BwdLayout bwd_layout(int64_t n, int64_t d, int64_t e, int64_t k, int64_t d_ff, int dtype) {
+static BwdLayout bwd_layout(int64_t n, int64_t d, int64_t e, int64_t k, int64_t d_ff, int dtype, bool hilo) {
     BwdLayout B;
     size_t off = 0;
     auto take = [&](size_t bytes) { size_t a = off; off = align_up(off + bytes, 256); return a; };
@@ -253,6 +257,7 @@ static BwdLayout bwd_layout(int64_t n, int64_t d, int64_t e, int64_t k, int64_t 
     // Intermediates: bf16 where they are matrix-core operands (dA as high part + remainder), fp32 on the plain path.
     const size_t is = B.mfma ? 2 : 4;
     B.dxe = take((size_t)e * k * d * is);
+    B.dxe_lo = take((B.mfma && hilo) ? (size_t)e * k * d * 2 : 0);
     B.dg = take((size_t)e * k * 4);
     B.da = take((size_t)e * k * d_ff * is);
     B.da_lo = take(B.mfma ? (size_t)e * k * d_ff * 2 : 0);
@@ -266,15 +271,15 @@ static BwdLayout bwd_layout(int64_t n, int64_t d, int64_t e, int64_t k, int64_t 
     return B;
 }
 
-size_t bwd_ws_bytes(int64_t n, int64_t d, int64_t e, int64_t k, int64_t d_ff, int dtype) {
-    return bwd_layout(n, d, e, k, d_ff, dtype).total;
+size_t bwd_ws_bytes(int64_t n, int64_t d, int64_t e, int64_t k, int64_t d_ff, int dtype, bool hilo) {
+    return bwd_layout(n, d, e, k, d_ff, dtype, hilo).total;
 }
 
 template <typename T>
 static int backward_typed(const T* dY, const T* X, const T* Wg, const T* W1, const T* W2, const float* S, const float* G,
                           const int32_t* I, const T* Xin, const T* A, const T* H, const T* Xe, T* dX, float* dWg,
                           float* dW1, float* dW2, int64_t n, int64_t d, int64_t e, int64_t k, int64_t d_ff, int act,
-                          int dtype, void* ws, const WsLayout& L, hipStream_t stream, hipEvent_t* marks) {
+                          int dtype, void* ws, const WsLayout& L, hipStream_t stream, hipEvent_t* marks, bool hilo) {
     // marks (optional, BWD_STAGES + 1 events): recorded on the stream before the first stage and after every stage
     int mark_at = 0;
     auto mark = [&]() {
@@ -283,7 +288,8 @@ static int backward_typed(const T* dY, const T* X, const T* Wg, const T* W1, con
     };
     mark();
     unsigned char* base = static_cast<unsigned char*>(ws) + L.bwd;
-    const BwdLayout B = bwd_layout(n, d, e, k, d_ff, dtype);
+    const BwdLayout B = bwd_layout(n, d, e, k, d_ff, dtype, hilo);
+    if (hilo && !B.mfma) return EC_ERR_UNSUPPORTED;  // the two-part operands exist on the matrix-core path only
     float* dG = reinterpret_cast<float*>(base + B.dg);
     float* dXin = reinterpret_cast<float*>(base + B.dxin);
     float* dZ = reinterpret_cast<float*>(base + B.dz);
@@ -311,17 +317,20 @@ static int backward_typed(const T* dY, const T* X, const T* Wg, const T* W1, con
         const dim3 grid((unsigned)blocks), block(256);
         void* dXe = base + B.dxe;
         if (mfma) {
+            T* dXe_lo = hilo ? reinterpret_cast<T*>(base + B.dxe_lo) : nullptr;
             if (d % V16 == 0)
-                hipLaunchKernelGGL((bwd_rows_kernel<T, V16, T>), grid, block, 0, stream, dY, Xe, G, I, (T*)dXe, dG, rows, D);
+                hipLaunchKernelGGL((bwd_rows_kernel<T, V16, T>), grid, block, 0, stream, dY, Xe, G, I, (T*)dXe, dG, rows, D,
+                                   dXe_lo);
             else
-                hipLaunchKernelGGL((bwd_rows_kernel<T, 1, T>), grid, block, 0, stream, dY, Xe, G, I, (T*)dXe, dG, rows, D);
+                hipLaunchKernelGGL((bwd_rows_kernel<T, 1, T>), grid, block, 0, stream, dY, Xe, G, I, (T*)dXe, dG, rows, D,
+                                   dXe_lo);
         } else {
             if (d % V16 == 0)
                 hipLaunchKernelGGL((bwd_rows_kernel<T, V16, float>), grid, block, 0, stream, dY, Xe, G, I, (float*)dXe, dG,
-                                   rows, D);
+                                   rows, D, (float*)nullptr);
             else
                 hipLaunchKernelGGL((bwd_rows_kernel<T, 1, float>), grid, block, 0, stream, dY, Xe, G, I, (float*)dXe, dG,
-                                   rows, D);
+                                   rows, D, (float*)nullptr);
         }
     }
     mark();  // 0: rows
@@ -332,9 +341,15 @@ static int backward_typed(const T* dY, const T* X, const T* Wg, const T* W1, con
                          *bXin = (const bf16_t*)Xin;
             bf16_t* dA = reinterpret_cast<bf16_t*>(base + B.da);       // high part: bf16(dA)
             bf16_t* dAlo = reinterpret_cast<bf16_t*>(base + B.da_lo);  // remainder: bf16(dA - high part)
-            // dW2[i] = H[i]^T dX_e[i]     (A stored [k][d_ff], B [k][d]) -> fp32 [d_ff][d]
-            gemm_bf16_launch<256, 256, 2, 1, true, false, EPI_F32, EC_ACT_IDENTITY>(bH, bdXe, dW2, nullptr, Gn, F, D, Mk,
-                                                                                    nullptr, 0, stream);
+            // dW2[i] = H[i]^T dX_e[i]     (A stored [k][d_ff], B [k][d]) -> fp32 [d_ff][d]; with the two-part dX_e the
+            // contraction runs over its high part and its remainder
+            if (hilo)
+                gemm_bf16_launch<256, 256, 2, 1, true, false, EPI_F32, EC_ACT_IDENTITY, SPLIT_RIGHT>(
+                    bH, bdXe, dW2, nullptr, Gn, F, D, Mk, nullptr, 0, stream, nullptr,
+                    reinterpret_cast<const bf16_t*>(base + B.dxe_lo), nullptr);
+            else
+                gemm_bf16_launch<256, 256, 2, 1, true, false, EPI_F32, EC_ACT_IDENTITY>(bH, bdXe, dW2, nullptr, Gn, F, D, Mk,
+                                                                                        nullptr, 0, stream);
             mark();  // 1: dW2
             // dA[i] = (dX_e[i] W2[i]^T) * act'(A[i]) with dX_e[r,:] = G[r] dY[I[r],:]: the rows of dY are gathered by
             // the tile loader (exact bf16 operands) and G[r] multiplies the fp32 result in the epilogue, so dA -- and
@@ -356,7 +371,7 @@ static int backward_typed(const T* dY, const T* X, const T* Wg, const T* W1, con
             // summed into dX.  A token's gradient row scales with its gate value while the error bar is relative to
             // the whole tensor, so a single bf16 rounding of dA (2^-9) is what decides the worst element of dX;
             // with the remainder the product sees dA to 2^-17, at twice the work of this one product.
-            gemm_bf16_launch<256, 256, 2, 1, false, true, EPI_F32, EC_ACT_IDENTITY, true>(
+            gemm_bf16_launch<256, 256, 2, 1, false, true, EPI_F32, EC_ACT_IDENTITY, SPLIT_LEFT>(
                 (const bf16_t*)dA, (const bf16_t*)W1, dXin, nullptr, Gn, Mk, D, F, nullptr, 0, stream, nullptr, dAlo, nullptr);
             mark();  // 4: dX_in
         }
@@ -450,15 +465,15 @@ int launch_backward(const void* dY, const void* X, const void* Wg, const void* W
                     const float* G, const int32_t* I, const void* Xin, const void* A, const void* H, const void* Xe,
                     void* dX, float* dWg, float* dW1, float* dW2, int64_t n, int64_t d, int64_t e, int64_t k,
                     int64_t d_ff, int act, int dtype, void* ws, const WsLayout& L, hipStream_t stream,
-                    hipEvent_t* marks) {
+                    hipEvent_t* marks, bool hilo) {
     if (dtype == EC_BF16)
         return backward_typed<bf16_t>((const bf16_t*)dY, (const bf16_t*)X, (const bf16_t*)Wg, (const bf16_t*)W1,
                                       (const bf16_t*)W2, S, G, I, (const bf16_t*)Xin, (const bf16_t*)A, (const bf16_t*)H,
                                       (const bf16_t*)Xe, (bf16_t*)dX, dWg, dW1, dW2, n, d, e, k, d_ff, act, dtype, ws, L,
-                                      stream, marks);
+                                      stream, marks, hilo);
     return backward_typed<float>((const float*)dY, (const float*)X, (const float*)Wg, (const float*)W1, (const float*)W2,
                                  S, G, I, (const float*)Xin, (const float*)A, (const float*)H, (const float*)Xe, (float*)dX,
-                                 dWg, dW1, dW2, n, d, e, k, d_ff, act, dtype, ws, L, stream, marks);
+                                 dWg, dW1, dW2, n, d, e, k, d_ff, act, dtype, ws, L, stream, marks, false);
 }
 
 }  // namespace ecmoe

@@ -324,12 +324,18 @@ int launch_combine(const void* Xe, const float* G, const int32_t* I, void* Xout,
                                offs, list, (TYPE*)Xout, (int)n, (int)d, tpr, addend, src_rows);                                 \
     } while (0)
     if (dtype == EC_BF16 && rows_f32) {
-        if (ix.use_slots) return EC_ERR_UNSUPPORTED;  // fp32 rows only come with the CSR lists (backward pass)
         int tpr = pick_threads_per_row(d / 8);
         long long blocks = ceil_div(n, 256 / tpr);
         if (blocks > (1 << 20)) blocks = 1 << 20;
-        hipLaunchKernelGGL((combine_kernel<bf16_t, 8, 0, float>), dim3((unsigned)blocks), dim3(256), 0, stream,
-                           (const float*)Xe, G, offs, list, (bf16_t*)Xout, (int)n, (int)d, tpr, addend, src_rows);
+        const dim3 grid((unsigned)blocks), block(256);
+#define EC_COMBINE_F32ROWS(CAPV)                                                                                   \
+    hipLaunchKernelGGL((combine_kernel<bf16_t, 8, CAPV, float>), grid, block, 0, stream, (const float*)Xe, G, offs, list, \
+                       (bf16_t*)Xout, (int)n, (int)d, tpr, addend, src_rows)
+        if (!ix.use_slots) EC_COMBINE_F32ROWS(0);
+        else if (ix.slot_cap == 4) EC_COMBINE_F32ROWS(4);
+        else if (ix.slot_cap == 8) EC_COMBINE_F32ROWS(8);
+        else EC_COMBINE_F32ROWS(16);
+#undef EC_COMBINE_F32ROWS
     } else if (dtype == EC_BF16) EC_COMBINE_LAUNCH(bf16_t, 8, d / 8);
     else if (d % 4 == 0) EC_COMBINE_LAUNCH(float, 4, d / 4);
     else EC_COMBINE_LAUNCH(float, 1, d);

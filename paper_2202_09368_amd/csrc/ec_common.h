@@ -34,7 +34,7 @@ inline int check_launch() {
 
 inline size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
 inline int64_t ceil_div(int64_t a, int64_t b) { return (a + b - 1) / b; }
-inline size_t elem_size(int dtype) { return dtype == EC_BF16 ? 2 : 4; }
+inline size_t elem_size(int dtype) { return (dtype == EC_BF16 || dtype == EC_BF16_HILO) ? 2 : 4; }
 inline bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
 
 // ---------------------------------------------------------------------------
@@ -49,6 +49,8 @@ struct WsLayout {
     size_t xin;        // dtype [e, k, d]
     size_t h;          // dtype [e, k, d_ff]
     size_t xe;         // dtype [e, k, d]
+    size_t h_lo;       // bf16 [e, k, d_ff]: act(A) - H                            (EC_BF16_HILO only)
+    size_t xe32;       // float [e, k, d]: X_e unrounded                           (EC_BF16_HILO only)
     size_t bitmap;     // uint32 [n, ceil(e/32)]: which experts chose a token      (CSR form, e > COMBINE_SLOT_CAP)
     size_t offsets;    // int32 [n+1]: CSR row starts of the token-major index
     size_t inv;        // int32 [e*k]: bucket rows (i*k+j) grouped by token, expert-ascending
@@ -62,7 +64,7 @@ struct WsLayout {
 WsLayout ws_layout(int64_t n, int64_t d, int64_t e, int64_t k, int64_t d_ff, int dtype, int with_backward);
 
 // Sizes of the backward-only region (defined with the backward kernels).
-size_t bwd_ws_bytes(int64_t n, int64_t d, int64_t e, int64_t k, int64_t d_ff, int dtype);
+size_t bwd_ws_bytes(int64_t n, int64_t d, int64_t e, int64_t k, int64_t d_ff, int dtype, bool hilo = false);
 
 // Token-major index of the routing handed from the top-k stage to the combine stage.
 constexpr int COMBINE_SLOT_CAP = 16;
@@ -103,9 +105,10 @@ int launch_combine_index(const int32_t* I, int64_t n, int64_t e, int64_t k, cons
 int launch_dispatch(const void* X, const int32_t* I, void* Xin, int64_t n, int64_t d, int64_t e, int64_t k,
                     int dtype, hipStream_t stream);
 bool ffn_can_gather(int dtype, int64_t n, int64_t k, int64_t d, int64_t d_ff);
+bool ffn_can_hilo(int dtype, int64_t k, int64_t d, int64_t d_ff);
 int launch_ffn(const void* Xin, const void* X, const int32_t* I, int64_t n, const void* W1, const void* W2, void* Xe,
                void* A_save, void* H, int64_t e, int64_t k, int64_t d, int64_t d_ff, int act, int dtype,
-               hipStream_t stream);
+               hipStream_t stream, void* H_lo = nullptr, float* Xe32 = nullptr);
 int launch_combine_csr(const int32_t* I, int64_t n, int64_t e, int64_t k, const CombineIndex& ix, hipStream_t stream);
 int launch_combine(const void* Xe, const float* G, const int32_t* I, void* Xout, int64_t n, int64_t d,
                    int64_t e, int64_t k, int dtype, const CombineIndex& ix, hipStream_t stream,
@@ -117,7 +120,7 @@ int launch_backward(const void* dY, const void* X, const void* Wg, const void* W
                     const float* S, const float* G, const int32_t* I, const void* Xin, const void* A,
                     const void* H, const void* Xe, void* dX, float* dWg, float* dW1, float* dW2,
                     int64_t n, int64_t d, int64_t e, int64_t k, int64_t d_ff, int act, int dtype,
-                    void* ws, const WsLayout& L, hipStream_t stream, hipEvent_t* marks = nullptr);
+                    void* ws, const WsLayout& L, hipStream_t stream, hipEvent_t* marks = nullptr, bool hilo = false);
 constexpr int BWD_STAGES = 9;  // rows, dW2, dA, dW1, dX_in, index, dZ, gate products, scatter
 
 // ---------------------------------------------------------------------------

@@ -213,22 +213,22 @@ static bool gemm_bf16_fast_ok(int64_t M, int64_t N, int64_t K, bool gather, int6
 
 template <int BM, int BN, int STAGES, int OCC>
 static int launch_gemm_bf16(const bf16_t* A, const bf16_t* B, bf16_t* C, bf16_t* Cpre, int G, int M, int N, int K,
-                            int act, const int32_t* gather, int gather_rows, hipStream_t stream) {
+                            int act, const int32_t* gather, int gather_rows, hipStream_t stream, bf16_t* Clo) {
     if (gemm_bf16_fast_ok(M, N, K, gather != nullptr, gather_rows)) {
 #define EC_GEMM_CASE(ACTV)                                                                                       \
-    if (Cpre) gemm_bf16_launch<BM, BN, STAGES, OCC, false, false, EPI_ACT_SAVE, ACTV>(A, B, C, Cpre, G, M, N, K,  \
-                                                                                     gather, gather_rows, stream); \
-    else gemm_bf16_launch<BM, BN, STAGES, OCC, false, false, EPI_ACT, ACTV>(A, B, C, nullptr, G, M, N, K, gather,  \
-                                                                           gather_rows, stream)
+    if (Cpre) gemm_bf16_launch<BM, BN, STAGES, OCC, false, false, EPI_ACT_SAVE, ACTV>(                           \
+                  A, B, C, Cpre, G, M, N, K, gather, gather_rows, stream, nullptr, nullptr, Clo);                \
+    else gemm_bf16_launch<BM, BN, STAGES, OCC, false, false, EPI_ACT, ACTV>(A, B, C, nullptr, G, M, N, K, gather, \
+                                                                           gather_rows, stream, nullptr, nullptr, Clo)
         if (act == EC_ACT_RELU) { EC_GEMM_CASE(EC_ACT_RELU); }
         else if (act == EC_ACT_GELU) { EC_GEMM_CASE(EC_ACT_GELU); }
         else { EC_GEMM_CASE(EC_ACT_IDENTITY); }
 #undef EC_GEMM_CASE
         return check_launch();
     }
-    // general shapes: predicated kernel, 128 x 128 tiles.  It reads its left operand as stored: a caller that asked
-    // for gathered rows gets an error instead of a wrong product.
-    if (gather != nullptr) return EC_ERR_UNSUPPORTED;
+    // general shapes: predicated kernel, 128 x 128 tiles.  It reads its left operand as stored and writes one
+    // output: a caller that asked for gathered rows or for the remainders gets an error instead of a wrong product.
+    if (gather != nullptr || Clo != nullptr) return EC_ERR_UNSUPPORTED;
     if ((int64_t)M * K >= ((int64_t)1 << 31) || (int64_t)K * N >= ((int64_t)1 << 31) || (int64_t)M * N >= ((int64_t)1 << 31))
         return EC_ERR_UNSUPPORTED;
     constexpr int GBM = 128, GBN = 128;
@@ -257,8 +257,7 @@ static int launch_gemm_bf16(const bf16_t* A, const bf16_t* B, bf16_t* C, bf16_t*
 
 // Tile configuration of a grouped product: the candidate with the lowest estimated time, taken as
 // (rounds of 256 compute units) x (tile area) / (relative rate of that configuration).
-static int gemm_bf16_dispatch(const bf16_t* A, const bf16_t* B, bf16_t* C, bf16_t* Cpre, int G, int M, int N,
-                              int K, int act, const int32_t* gather, int gather_rows, hipStream_t stream) {
+static int gemm_tile_pick(int G, int M, int N, int K) {
     auto cost = [&](int bm, int bn, int occ, double rate) {
         double tiles = (double)G * ((M + bm - 1) / bm) * ((N + bn - 1) / bn);
         double rounds = std::ceil(tiles / (256.0 * occ)) * occ;
@@ -273,13 +272,37 @@ static int gemm_bf16_dispatch(const bf16_t* A, const bf16_t* B, bf16_t* C, bf16_
     // K = 768 (16 x 1024 x 3072): 103 us against 105 (256 x 256) and 111 (256 x 128 pairs); from K = 1024 on
     // (64 x 512 x 4096) the 256 x 256 tile wins, 344 us against 356 and 369.
     if (pick == 0 && K <= 768 && cost(128, 128, 2, 1.0) <= 1.25 * c0) pick = 2;
-    switch (pick) {
-        case 0: return launch_gemm_bf16<256, 256, 2, 1>(A, B, C, Cpre, G, M, N, K, act, gather, gather_rows, stream);
-        case 1: return launch_gemm_bf16<256, 128, 2, 1>(A, B, C, Cpre, G, M, N, K, act, gather, gather_rows, stream);
-        case 2: return launch_gemm_bf16<128, 128, 1, 2>(A, B, C, Cpre, G, M, N, K, act, gather, gather_rows, stream);
-        case 4: return launch_gemm_bf16<256, 192, 2, 1>(A, B, C, Cpre, G, M, N, K, act, gather, gather_rows, stream);
-        default: return launch_gemm_bf16<256, 256, 2, 1>(A, B, C, Cpre, G, M, N, K, act, gather, gather_rows, stream);
+    return pick;
+}
+
+// Clo (optional): receives act(acc) - C, the part of the activated value that the bf16 rounding of C dropped.
+static int gemm_bf16_dispatch(const bf16_t* A, const bf16_t* B, bf16_t* C, bf16_t* Cpre, int G, int M, int N,
+                              int K, int act, const int32_t* gather, int gather_rows, hipStream_t stream,
+                              bf16_t* Clo = nullptr) {
+    switch (gemm_tile_pick(G, M, N, K)) {
+        case 1: return launch_gemm_bf16<256, 128, 2, 1>(A, B, C, Cpre, G, M, N, K, act, gather, gather_rows, stream, Clo);
+        case 2: return launch_gemm_bf16<128, 128, 1, 2>(A, B, C, Cpre, G, M, N, K, act, gather, gather_rows, stream, Clo);
+        case 4: return launch_gemm_bf16<256, 192, 2, 1>(A, B, C, Cpre, G, M, N, K, act, gather, gather_rows, stream, Clo);
+        default: return launch_gemm_bf16<256, 256, 2, 1>(A, B, C, Cpre, G, M, N, K, act, gather, gather_rows, stream, Clo);
     }
+}
+
+// The second product of Eq. 3 with its left operand carried as high part + remainder (A + Alo): C32 (fp32) = the
+// product unrounded, Cb (bf16, optional) = the same rounded.  The tile is chosen for the doubled contraction.
+static int gemm_bf16_dispatch_split(const bf16_t* A, const bf16_t* Alo, const bf16_t* B, float* C32, bf16_t* Cb, int G,
+                                    int M, int N, int K, hipStream_t stream) {
+    if (!gemm_bf16_shape_ok(M, N, K)) return EC_ERR_UNSUPPORTED;
+#define EC_SPLIT_CASE(BM, BN, ST, OCC)                                                                              \
+    gemm_bf16_launch<BM, BN, ST, OCC, false, false, EPI_F32, EC_ACT_IDENTITY, SPLIT_LEFT>(A, B, C32, nullptr, G, M, N, K, \
+                                                                                         nullptr, 0, stream, nullptr, Alo, Cb)
+    switch (gemm_tile_pick(G, M, N, 2 * K)) {
+        case 1: EC_SPLIT_CASE(256, 128, 2, 1); break;
+        case 2: EC_SPLIT_CASE(128, 128, 1, 2); break;
+        case 4: EC_SPLIT_CASE(256, 192, 2, 1); break;
+        default: EC_SPLIT_CASE(256, 256, 2, 1); break;
+    }
+#undef EC_SPLIT_CASE
+    return check_launch();
 }
 
 // ===========================================================================
@@ -360,24 +383,34 @@ bool ffn_can_gather(int dtype, int64_t n, int64_t k, int64_t d, int64_t d_ff) {
 }
 
 
+// True when the products can carry H as high part + remainder (the matrix-core kernel covers both shapes).
+bool ffn_can_hilo(int dtype, int64_t k, int64_t d, int64_t d_ff) {
+    return dtype == EC_BF16 && k > 0 && gemm_bf16_shape_ok(k, d_ff, d) && gemm_bf16_shape_ok(k, d, d_ff);
+}
+
 // Xin == nullptr: gather mode, rows of the buckets are read from X through I (needs ffn_can_gather).
+// H_lo / Xe32 (both or neither; need ffn_can_hilo): the first product also leaves H_lo = act(A) - H, the second
+// multiplies (H + H_lo) by W2 and writes X_e unrounded to Xe32 [e,k,d] (fp32), and rounded to Xe if Xe is given.
 int launch_ffn(const void* Xin, const void* X, const int32_t* I, int64_t n, const void* W1, const void* W2, void* Xe,
                void* A_save, void* H, int64_t e, int64_t k, int64_t d, int64_t d_ff, int act, int dtype,
-               hipStream_t stream) {
+               hipStream_t stream, void* H_lo, float* Xe32) {
     const int G = (int)e, M = (int)k;
     if (dtype == EC_BF16) {
         int rc;
         if (Xin == nullptr)
             rc = gemm_bf16_dispatch((const bf16_t*)X, (const bf16_t*)W1, (bf16_t*)H, (bf16_t*)A_save, G, M, (int)d_ff,
-                                    (int)d, act, I, (int)n, stream);
+                                    (int)d, act, I, (int)n, stream, (bf16_t*)H_lo);
         else
             rc = gemm_bf16_dispatch((const bf16_t*)Xin, (const bf16_t*)W1, (bf16_t*)H, (bf16_t*)A_save, G, M, (int)d_ff,
-                                    (int)d, act, nullptr, 0, stream);
+                                    (int)d, act, nullptr, 0, stream, (bf16_t*)H_lo);
         if (rc != EC_OK) return rc;
+        if (H_lo != nullptr)
+            return gemm_bf16_dispatch_split((const bf16_t*)H, (const bf16_t*)H_lo, (const bf16_t*)W2, Xe32, (bf16_t*)Xe, G,
+                                            M, (int)d, (int)d_ff, stream);
         return gemm_bf16_dispatch((const bf16_t*)H, (const bf16_t*)W2, (bf16_t*)Xe, nullptr, G, M, (int)d, (int)d_ff,
                                   EC_ACT_IDENTITY, nullptr, 0, stream);
     }
-    if (Xin == nullptr) return EC_ERR_UNSUPPORTED;
+    if (Xin == nullptr || H_lo != nullptr) return EC_ERR_UNSUPPORTED;
     int rc = launch_gemm_f32((const float*)Xin, (const float*)W1, (float*)H, (float*)A_save, G, M, (int)d_ff, (int)d, act,
                              stream);
     if (rc != EC_OK) return rc;

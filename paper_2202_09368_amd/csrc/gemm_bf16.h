@@ -34,11 +34,11 @@ constexpr int GEMM_LDS_STRIDE = GEMM_BK + 8;  // bf16 elements per LDS row of a 
 typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
 
 enum GemmEpilogue {
-    EPI_ACT = 0,       // C (bf16) = act(acc)
+    EPI_ACT = 0,       // C (bf16) = act(acc); optionally C3 (bf16) = act(acc) - C, what the rounding of C dropped
     EPI_ACT_SAVE = 1,  // additionally C2 (bf16) = acc
     EPI_MULGRAD = 2,   // C (bf16) = v = acc * act'(C2[m][n]) [* row_scale[m]],  C2 = bf16 pre-activations (read);
                        // optionally C3 (bf16) = v - C, the part of v that the rounding of C dropped
-    EPI_F32 = 3,       // C (fp32) = acc
+    EPI_F32 = 3,       // C (fp32) = acc; optionally C3 (bf16) = acc rounded
     EPI_SOFTMAX = 4    // one group, N <= BN: C (fp32, [N][M]) = softmax over n of acc[m][:], transposed;
                        // C2 (fp32, [M][N], optional) the same untransposed.  `gather` is not used for
                        // loads here: it names `gather_rows` 32-bit words that the launch sets to zero.
@@ -84,16 +84,22 @@ __device__ __forceinline__ float apply_act_grad_bf16(float a) {
     return 1.0f;
 }
 
-// SPLIT_A (A_MC = false only): the left operand is the sum of two bf16 matrices, A[g] + A2[g] (a value carried as
-// high part + remainder); the contraction takes 64 columns of one, then the same 64 columns of the other, against
-// the same rows of B, so the product sees the left operand to 2^-17 at twice the work.
-template <int BM, int BN, int STAGES, int OCC, bool A_MC, bool B_KC, int EPI, int ACT, bool SPLIT_A = false>
+// SPLIT: one operand is the sum of two bf16 matrices (a value carried as high part + remainder), the second part
+// given as `X2all`: the contraction takes 64 steps of k with the first part, then the same 64 steps with the second,
+// against the same piece of the other operand, so the product sees that operand to 2^-17 at twice the work.
+//   SPLIT_LEFT   the left operand, contraction-contiguous (A_MC = false): A[g] + X2[g]
+//   SPLIT_RIGHT  the right operand in its [K][N] form (B_KC = false):     B[g] + X2[g]
+enum GemmSplit { SPLIT_NONE = 0, SPLIT_LEFT = 1, SPLIT_RIGHT = 2 };
+
+template <int BM, int BN, int STAGES, int OCC, bool A_MC, bool B_KC, int EPI, int ACT, int SPLIT = SPLIT_NONE>
 __global__ void __launch_bounds__(256, OCC)
 gemm_bf16_kernel(const bf16_t* __restrict__ Aall, const bf16_t* __restrict__ Ball, void* __restrict__ Call,
                  void* __restrict__ C2all, int M, int N, int K, int G, int tiles_m, int tiles_n,
                  const int32_t* __restrict__ gather, int gather_rows, const float* __restrict__ row_scale,
-                 const bf16_t* __restrict__ A2all, void* __restrict__ C3all) {
-    static_assert(!SPLIT_A || !A_MC, "the two-part left operand is contraction-contiguous");
+                 const bf16_t* __restrict__ X2all, void* __restrict__ C3all) {
+    static_assert(SPLIT != SPLIT_LEFT || !A_MC, "the two-part left operand is contraction-contiguous");
+    static_assert(SPLIT != SPLIT_RIGHT || !B_KC, "the two-part right operand keeps k as its row index");
+    constexpr bool SPLIT_A = SPLIT == SPLIT_LEFT, SPLIT_B = SPLIT == SPLIT_RIGHT;
     constexpr int WM = BM / 2, WN = BN / 2;
     constexpr int TM = WM / 32, TN = WN / 32;
     constexpr int A_CHUNKS = BM / 32, B_CHUNKS = BN / 32;  // 16-byte chunks per thread and stage
@@ -105,8 +111,8 @@ gemm_bf16_kernel(const bf16_t* __restrict__ Aall, const bf16_t* __restrict__ Bal
     constexpr bool F32_STRIP = EPI == EPI_MULGRAD || EPI == EPI_F32;
     constexpr int EPI_STRIDE = F32_STRIP ? WN + 4 : WN + 8;  // elements per staged output row
     static_assert(TM >= 1 && TN >= 1, "tile too small");
-    static_assert(EPI == EPI_SOFTMAX || 4 * 32 * EPI_STRIDE * (F32_STRIP ? 4 : 2) <= STAGES * STAGE * 2,
-                  "epilogue staging must fit");
+    static_assert(EPI == EPI_SOFTMAX || (F32_STRIP ? 1 : 2) * 4 * 32 * EPI_STRIDE * (F32_STRIP ? 4 : 2) <= STAGES * STAGE * 2,
+                  "epilogue staging must fit (bf16 outputs: two sets of strips, values and remainders)");
     static_assert(STAGES == 1 || STAGES == 2, "one or two LDS stages");
 
     extern __shared__ __attribute__((aligned(16))) unsigned char smem_raw[];
@@ -145,10 +151,13 @@ gemm_bf16_kernel(const bf16_t* __restrict__ Aall, const bf16_t* __restrict__ Bal
         ? __builtin_amdgcn_make_buffer_rsrc(const_cast<bf16_t*>(Aall), 0, gather_rows * K * 2, 0x00020000)
         : __builtin_amdgcn_make_buffer_rsrc(const_cast<bf16_t*>(Aall + (size_t)g * M * K), 0, M * K * 2, 0x00020000);
     const __amdgpu_buffer_rsrc_t rsrcA2 = SPLIT_A
-        ? __builtin_amdgcn_make_buffer_rsrc(const_cast<bf16_t*>(A2all + (size_t)g * M * K), 0, M * K * 2, 0x00020000)
+        ? __builtin_amdgcn_make_buffer_rsrc(const_cast<bf16_t*>(X2all + (size_t)g * M * K), 0, M * K * 2, 0x00020000)
         : rsrcA;
     const __amdgpu_buffer_rsrc_t rsrcB = __builtin_amdgcn_make_buffer_rsrc(
         const_cast<bf16_t*>(Ball + (size_t)g * K * N), 0, K * N * 2, 0x00020000);
+    const __amdgpu_buffer_rsrc_t rsrcB2 = SPLIT_B
+        ? __builtin_amdgcn_make_buffer_rsrc(const_cast<bf16_t*>(X2all + (size_t)g * K * N), 0, K * N * 2, 0x00020000)
+        : rsrcB;
     const int a_kstep = A_MC ? M * 2 : 2;  // bytes per unit of k in the scalar stage offset
     const int b_kstep = B_KC ? 2 : N * 2;
 
@@ -202,15 +211,16 @@ gemm_bf16_kernel(const bf16_t* __restrict__ Aall, const bf16_t* __restrict__ Bal
     // 2j and 2j+1 multiply the first and the second part's columns 64j.. by the same 64 rows of B, which the second
     // of them finds in the cache.
     auto load_tiles = [&](int k0) {
-        const bool second = SPLIT_A && ((k0 / GEMM_BK) & 1) != 0;
-        const int kk = SPLIT_A ? (k0 / (2 * GEMM_BK)) * GEMM_BK : k0;
+        const bool second = SPLIT != SPLIT_NONE && ((k0 / GEMM_BK) & 1) != 0;
+        const int kk = SPLIT != SPLIT_NONE ? (k0 / (2 * GEMM_BK)) * GEMM_BK : k0;
 #pragma unroll
         for (int r = 0; r < A_CHUNKS; ++r)
-            areg[r] = second ? __builtin_amdgcn_raw_buffer_load_b128(rsrcA2, a_voff[r], kk * a_kstep, 0)
-                             : __builtin_amdgcn_raw_buffer_load_b128(rsrcA, a_voff[r], kk * a_kstep, 0);
+            areg[r] = (SPLIT_A && second) ? __builtin_amdgcn_raw_buffer_load_b128(rsrcA2, a_voff[r], kk * a_kstep, 0)
+                                          : __builtin_amdgcn_raw_buffer_load_b128(rsrcA, a_voff[r], kk * a_kstep, 0);
 #pragma unroll
         for (int r = 0; r < B_CHUNKS; ++r)
-            breg[r] = __builtin_amdgcn_raw_buffer_load_b128(rsrcB, b_voff[r], kk * b_kstep, 0);
+            breg[r] = (SPLIT_B && second) ? __builtin_amdgcn_raw_buffer_load_b128(rsrcB2, b_voff[r], kk * b_kstep, 0)
+                                          : __builtin_amdgcn_raw_buffer_load_b128(rsrcB, b_voff[r], kk * b_kstep, 0);
     };
     auto store_tiles = [&](int buf) {
         bf16_t* base = smem + buf * STAGE;
@@ -278,13 +288,15 @@ gemm_bf16_kernel(const bf16_t* __restrict__ Aall, const bf16_t* __restrict__ Bal
         else if (r < N_CHUNKS) *reinterpret_cast<u32x4*>(&dst[b_lds[r - A_CHUNKS]]) = breg[r - A_CHUNKS];
     };
     auto stage_load = [&](int r, int k_next) {
-        const bool second = SPLIT_A && ((k_next / GEMM_BK) & 1) != 0;
-        const int kk = SPLIT_A ? (k_next / (2 * GEMM_BK)) * GEMM_BK : k_next;
+        const bool second = SPLIT != SPLIT_NONE && ((k_next / GEMM_BK) & 1) != 0;
+        const int kk = SPLIT != SPLIT_NONE ? (k_next / (2 * GEMM_BK)) * GEMM_BK : k_next;
         if (r < A_CHUNKS)
-            areg[r] = second ? __builtin_amdgcn_raw_buffer_load_b128(rsrcA2, a_voff[r], kk * a_kstep, 0)
-                             : __builtin_amdgcn_raw_buffer_load_b128(rsrcA, a_voff[r], kk * a_kstep, 0);
+            areg[r] = (SPLIT_A && second) ? __builtin_amdgcn_raw_buffer_load_b128(rsrcA2, a_voff[r], kk * a_kstep, 0)
+                                          : __builtin_amdgcn_raw_buffer_load_b128(rsrcA, a_voff[r], kk * a_kstep, 0);
         else if (r < N_CHUNKS)
-            breg[r - A_CHUNKS] = __builtin_amdgcn_raw_buffer_load_b128(rsrcB, b_voff[r - A_CHUNKS], kk * b_kstep, 0);
+            breg[r - A_CHUNKS] =
+                (SPLIT_B && second) ? __builtin_amdgcn_raw_buffer_load_b128(rsrcB2, b_voff[r - A_CHUNKS], kk * b_kstep, 0)
+                                    : __builtin_amdgcn_raw_buffer_load_b128(rsrcB, b_voff[r - A_CHUNKS], kk * b_kstep, 0);
     };
     // One step (16 contraction elements) written in issue order.  After every MFMA comes at most one
     // fragment read for the following step (taken from `next_stage` at step `next_s`) and, in the
@@ -312,7 +324,7 @@ gemm_bf16_kernel(const bf16_t* __restrict__ Aall, const bf16_t* __restrict__ Bal
 
     // Loads past the last stage read zeros or in-range data of the same group: harmless, never consumed.
     // a ragged K is legal only when both operands keep k as the row index; a two-part left operand doubles the stages
-    const int nk = (SPLIT_A ? 2 : 1) * ((K + GEMM_BK - 1) / GEMM_BK);
+    const int nk = (SPLIT != SPLIT_NONE ? 2 : 1) * ((K + GEMM_BK - 1) / GEMM_BK);
     if (STAGES == 2) {
         // Both of the first two stages are requested at once (one trip to memory instead of two in a row): stage 0
         // into a second set of registers that only lives here, stage 1 into the set the loop works with.
@@ -429,13 +441,16 @@ gemm_bf16_kernel(const bf16_t* __restrict__ Aall, const bf16_t* __restrict__ Bal
     } else if (!F32_STRIP) {
         bf16_t* __restrict__ C = reinterpret_cast<bf16_t*>(Call) + gofs;
         bf16_t* __restrict__ Cpre = EPI == EPI_ACT_SAVE ? reinterpret_cast<bf16_t*>(C2all) + gofs : nullptr;
+        bf16_t* __restrict__ Clo = C3all != nullptr ? reinterpret_cast<bf16_t*>(C3all) + gofs : nullptr;
         bf16_t* strip = smem + wave * 32 * EPI_STRIDE;
+        bf16_t* strip_lo = smem + (4 + wave) * 32 * EPI_STRIDE;  // second set of strips, for the remainders
         constexpr int CHUNKS_PER_ROW = WN / 8;
         constexpr int ROWS_PER_PASS = 64 / CHUNKS_PER_ROW;  // lanes past ROWS_PER_PASS rows idle (WN = 96)
         const int er = lane / CHUNKS_PER_ROW, ec = lane % CHUNKS_PER_ROW;
 #pragma unroll
         for (int pass = 0; pass < (EPI == EPI_ACT_SAVE ? 2 : 1); ++pass) {
             const bool pre = EPI == EPI_ACT_SAVE && pass == 0;
+            const bool with_lo = !pre && Clo != nullptr;  // uniform
             bf16_t* __restrict__ dst = pre ? Cpre : C;
 #pragma unroll
             for (int i = 0; i < TM; ++i) {
@@ -444,12 +459,20 @@ gemm_bf16_kernel(const bf16_t* __restrict__ Aall, const bf16_t* __restrict__ Bal
 #pragma unroll
                     for (int q = 0; q < 4; ++q) {
                         bf16x4 v;
+                        float y[4];
 #pragma unroll
                         for (int t = 0; t < 4; ++t) {
                             const float x = acc[i][j][4 * q + t];
-                            v[t] = static_cast<bf16_t>(pre ? x : apply_act_bf16<ACT>(x));
+                            y[t] = pre ? x : apply_act_bf16<ACT>(x);
+                            v[t] = static_cast<bf16_t>(y[t]);
                         }
                         *reinterpret_cast<bf16x4*>(&strip[col * EPI_STRIDE + j * 32 + 8 * q + 4 * half]) = v;
+                        if (with_lo) {
+                            bf16x4 vl;
+#pragma unroll
+                            for (int t = 0; t < 4; ++t) vl[t] = static_cast<bf16_t>(y[t] - static_cast<float>(v[t]));
+                            *reinterpret_cast<bf16x4*>(&strip_lo[col * EPI_STRIDE + j * 32 + 8 * q + 4 * half]) = vl;
+                        }
                     }
                 __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
                 __builtin_amdgcn_wave_barrier();
@@ -458,9 +481,13 @@ gemm_bf16_kernel(const bf16_t* __restrict__ Aall, const bf16_t* __restrict__ Bal
                     const int row = rr + er;
                     const int gm = m0 + wr * WM + i * 32 + row;
                     const int gn = n0 + wc * WN + ec * 8;
-                    if (er < ROWS_PER_PASS && row < 32 && gm < M && gn < N)
+                    if (er < ROWS_PER_PASS && row < 32 && gm < M && gn < N) {
                         *reinterpret_cast<uint4*>(dst + (size_t)gm * N + gn) =
                             *reinterpret_cast<const uint4*>(&strip[row * EPI_STRIDE + ec * 8]);
+                        if (with_lo)
+                            *reinterpret_cast<uint4*>(Clo + (size_t)gm * N + gn) =
+                                *reinterpret_cast<const uint4*>(&strip_lo[row * EPI_STRIDE + ec * 8]);
+                    }
                 }
                 __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
                 __builtin_amdgcn_wave_barrier();
@@ -512,9 +539,16 @@ gemm_bf16_kernel(const bf16_t* __restrict__ Aall, const bf16_t* __restrict__ Bal
                     const int row = rr + er;
                     const int gm = m0 + wr * WM + i * 32 + row;
                     const int gn = n0 + wc * WN + ec * 4;
-                    if (er < ROWS_PER_PASS && row < 32 && gm < M && gn < N)
-                        *reinterpret_cast<floatx4*>(C + (size_t)gm * N + gn) =
-                            *reinterpret_cast<const floatx4*>(&strip[row * EPI_STRIDE + ec * 4]);
+                    if (er < ROWS_PER_PASS && row < 32 && gm < M && gn < N) {
+                        const floatx4 val = *reinterpret_cast<const floatx4*>(&strip[row * EPI_STRIDE + ec * 4]);
+                        *reinterpret_cast<floatx4*>(C + (size_t)gm * N + gn) = val;
+                        if (C3all != nullptr) {  // the same values rounded to bf16 (uniform branch)
+                            bf16x4 h;
+#pragma unroll
+                            for (int t = 0; t < 4; ++t) h[t] = static_cast<bf16_t>(val[t]);
+                            *reinterpret_cast<bf16x4*>(reinterpret_cast<bf16_t*>(C3all) + gofs + (size_t)gm * N + gn) = h;
+                        }
+                    }
                 }
             } else {
                 bf16_t* __restrict__ C = reinterpret_cast<bf16_t*>(Call) + gofs;
@@ -583,20 +617,19 @@ inline void gemm_allow_lds(const void* kern, size_t lds, std::atomic<bool>* done
     done[dev].store(true, std::memory_order_release);
 }
 
-// A2 (with SPLIT_A): the second part of the left operand.  C3 (EPI_MULGRAD, optional): receives what the rounding of C
-// dropped.
-template <int BM, int BN, int STAGES, int OCC, bool A_MC, bool B_KC, int EPI, int ACT, bool SPLIT_A = false>
+// X2 (with SPLIT): the second part of the split operand.  C3 (optional): see GemmEpilogue.
+template <int BM, int BN, int STAGES, int OCC, bool A_MC, bool B_KC, int EPI, int ACT, int SPLIT = SPLIT_NONE>
 static void gemm_bf16_launch(const bf16_t* A, const bf16_t* B, void* C, void* C2, int G, int M, int N, int K,
                              const int32_t* gather, int gather_rows, hipStream_t stream,
-                             const float* row_scale = nullptr, const bf16_t* A2 = nullptr, void* C3 = nullptr) {
+                             const float* row_scale = nullptr, const bf16_t* X2 = nullptr, void* C3 = nullptr) {
     const int tiles_m = (M + BM - 1) / BM, tiles_n = (N + BN - 1) / BN;
     const int total = G * tiles_m * tiles_n;
     const size_t lds = gemm_bf16_lds_bytes<BM, BN, STAGES>();
-    auto kern = gemm_bf16_kernel<BM, BN, STAGES, OCC, A_MC, B_KC, EPI, ACT, SPLIT_A>;
+    auto kern = gemm_bf16_kernel<BM, BN, STAGES, OCC, A_MC, B_KC, EPI, ACT, SPLIT>;
     static std::atomic<bool> lds_allowed[64];
     gemm_allow_lds(reinterpret_cast<const void*>(kern), lds, lds_allowed);
     hipLaunchKernelGGL(kern, dim3((unsigned)((total + 7) / 8 * 8)), dim3(256), lds, stream, A, B, C, C2, M, N, K, G,
-                       tiles_m, tiles_n, gather, gather_rows, row_scale, A2, C3);
+                       tiles_m, tiles_n, gather, gather_rows, row_scale, X2, C3);
 }
 
 }  // namespace ecmoe

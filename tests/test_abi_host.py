@@ -57,6 +57,16 @@ def test_workspace_sizes(m):
     assert m.ec_moe_workspace_bytes(256, 64, 8, 512, 256, m.EC_F32) == 0      # k > n
     assert m.ec_moe_workspace_bytes(256, 64, 8, 64, 256, 7) == 0             # unknown dtype
     assert m.ec_moe_workspace_bytes(256, 64, 2000, 1, 256, m.EC_F32) == 0    # too many experts
+    # two-part intermediates: room for the remainder of H and for the unrounded X_e on top of the bf16 layout; nothing
+    # extra for identity experts; no such layer when a width is not a multiple of 64
+    hilo = m.ec_moe_workspace_bytes(8192, 768, 16, 1024, 3072, m.EC_BF16_HILO)
+    assert hilo >= big + 16 * 1024 * (3072 * 2 + 768 * 4) and hilo % 256 == 0
+    assert m.ec_moe_workspace_bytes(8192, 768, 16, 1024, 3072, m.EC_BF16_HILO, True) > \
+        m.ec_moe_workspace_bytes(8192, 768, 16, 1024, 3072, m.EC_BF16, True) + (hilo - big)   # and of dX_e
+    assert m.ec_moe_workspace_bytes(8192, 768, 16, 1024, 0, m.EC_BF16_HILO) == \
+        m.ec_moe_workspace_bytes(8192, 768, 16, 1024, 0, m.EC_BF16)
+    assert m.ec_moe_workspace_bytes(256, 72, 4, 64, 136, m.EC_BF16_HILO) == 0
+    assert m.ec_moe_workspace_bytes(256, 72, 4, 64, 136, m.EC_BF16) > 0
 
 
 def test_invalid_arguments_are_rejected_on_the_host(m):
@@ -92,6 +102,14 @@ def test_invalid_arguments_are_rejected_on_the_host(m):
     assert fwd(P, None, 2.0, 1, P, 1 << 30) == INV
     assert fwd(P, P, 2.0, 1, None, 0) == WS
     assert fwd(P, P, 2.0, 1, P, 64) == WS
+    # two-part intermediates: widths outside the matrix-core path, and the two routing variants, are refused
+    UNS = -4
+    assert lib.ec_moe_forward(P, P, P, P, 2.0, P, None, None, None, None, None, None, None, 64, 16, 4, 32, 1,
+                              m.EC_BF16_HILO, P, 1 << 30, None) == UNS
+    assert lib.ec_moe_expert_ffn(P, P, P, P, None, None, 2, 4, 16, 32, 1, m.EC_BF16_HILO, P, 1 << 20, None) == UNS
+    assert lib.ec_moe_forward_token_choice(P, P, P, P, 2.0, 2, P, None, None, None, None, None, None, None, None, 64, 64,
+                                           16, 128, 1, m.EC_BF16_HILO, P, 1 << 30, None) == UNS
+    assert lib.ec_moe_backward(*([P] * 16 + [64, 16, 4, 32, 32, 1, m.EC_BF16_HILO, P, 1 << 40, None])) == UNS
     # grouped top-k: the groups must cut the tokens into equal runs; k_g within a run
     assert lib.ec_moe_topk_tokens_grouped(P, 10, 2, 3, 1, P, P, None, 0, None) == INV
     assert lib.ec_moe_topk_tokens_grouped(P, 12, 2, 0, 1, P, P, None, 0, None) == INV

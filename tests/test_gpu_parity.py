@@ -235,6 +235,73 @@ def test_cfg3_full(m, ref):
     _stagewise(m, ref, w, wl.make_inputs(w))
 
 
+def _layer_hilo(m, ref, w, inp):
+    """EC_BF16_HILO: ec_moe_forward and the stage-wise expert FFN against the oracle, every element inside the bar."""
+    n, d, e, k = w.n, w.d, w.e, w.k
+    t = {key: to_dev(inp[key]) for key in ("X", "Wg", "W1", "W2")}
+    ws = m.alloc_workspace(n, d, e, k, w.d_ff, m.EC_BF16_HILO)
+    Xout = torch.full((n, d), float("nan"), dtype=torch.bfloat16, device="cuda")
+    S = torch.empty((n, e), dtype=torch.float32, device="cuda")
+    G = torch.empty((e, k), dtype=torch.float32, device="cuda")
+    I = torch.empty((e, k), dtype=torch.int32, device="cuda")
+    m.ec_moe_forward(t["X"], t["Wg"], t["W1"], t["W2"], w.c, Xout, w.act, ws, S_out=S, G_out=G, I_out=I, hilo=True)
+    torch.cuda.synchronize()
+    S_h, G_h, I_h = to_host(S), to_host(G), to_host(I)
+    G_o, I_o = ref.topk_tokens(S_h, k)
+    assert (I_h == I_o).all() and (G_h.view(np.uint32) == G_o.view(np.uint32)).all()
+    Xin_h = ref.dispatch(inp["X"], I_h)
+    Xe_ref = ref.expert_ffn(Xin_h, inp["W1"], inp["W2"], w.act)
+    err = max_rel_err(to_host(Xout), ref.combine(Xe_ref, G_h, I_h, n))
+    _p(f"[{w.name} hilo] X_out (ec_moe_forward) max rel err {err:.3e}")
+    assert err <= out_tol(w)
+    # the same with the optional outputs, and the stage-wise product, whose X_e is the bf16 tensor of the interface
+    Xout2 = torch.full((n, d), float("nan"), dtype=torch.bfloat16, device="cuda")
+    Xe2 = torch.empty((e, k, d), dtype=torch.bfloat16, device="cuda")
+    m.ec_moe_forward(t["X"], t["Wg"], t["W1"], t["W2"], w.c, Xout2, w.act, ws, Xe_out=Xe2, hilo=True)
+    Xe3 = torch.empty((e, k, d), dtype=torch.bfloat16, device="cuda")
+    m.ec_moe_expert_ffn(to_dev(Xin_h), t["W1"], t["W2"], Xe3, w.act, ws, hilo=True)
+    torch.cuda.synchronize()
+    assert (to_host(Xout2) == to_host(Xout)).all()
+    assert (to_host(Xe3) == to_host(Xe2)).all()
+    err = max_rel_err(to_host(Xe2), Xe_ref)
+    _p(f"[{w.name} hilo] X_e max rel err {err:.3e}")
+    assert err <= 4e-3                                            # its one bf16 rounding
+
+
+@pytest.mark.parametrize("name,kw", [
+    ("cfg2", dict(n=2048, d=256, e=8, d_ff=512, act=wl.ACT_RELU)),      # slot lists
+    ("cfg3", dict(n=4096, d=128, e=64, d_ff=256)),                       # CSR lists
+    ("cfg2", dict(n=1000, d=192, e=16, d_ff=320)),                       # ragged bucket rows (k = 125)
+])
+def test_reduced_shapes_hilo(m, ref, name, kw):
+    w = sized(wl.WORKLOADS[name], **kw)
+    _layer_hilo(m, ref, w, wl.make_inputs(w))
+
+
+def test_cfg2_full_hilo(m, ref):
+    w = wl.WORKLOADS["cfg2"]
+    _layer_hilo(m, ref, w, wl.make_inputs(w))
+
+
+def test_cfg3_full_hilo(m, ref):
+    # the case EC_BF16 misses on its worst element: all 64 experts, all 16.8 M outputs inside the bar
+    w = wl.WORKLOADS["cfg3"]
+    _layer_hilo(m, ref, w, wl.make_inputs(w))
+
+
+def test_hilo_needs_the_matrix_core_shapes(m):
+    # widths that are not multiples of 64 have no two-part operands: refused, not silently computed the plain way
+    w = sized(wl.WORKLOADS["cfg2"], n=256, d=72, e=4, d_ff=136)
+    inp = wl.make_inputs(w)
+    t = {key: to_dev(inp[key]) for key in ("X", "Wg", "W1", "W2")}
+    assert m.ec_moe_workspace_bytes(w.n, w.d, w.e, w.k, w.d_ff, m.EC_BF16_HILO) == 0
+    ws = torch.empty(4 * m.ec_moe_workspace_bytes(w.n, w.d, w.e, w.k, w.d_ff, m.EC_BF16), dtype=torch.uint8, device="cuda")
+    Xout = torch.empty((w.n, w.d), dtype=torch.bfloat16, device="cuda")
+    with pytest.raises(m.EcMoeError) as ei:
+        m.ec_moe_forward(t["X"], t["Wg"], t["W1"], t["W2"], w.c, Xout, w.act, ws, hilo=True)
+    assert ei.value.status == -4
+
+
 def test_cfg5_full_routing_only(m, ref):
     # full size: 65536 tokens, 256 experts, skewed scores, identity experts
     w = wl.WORKLOADS["cfg5"]
