@@ -54,9 +54,9 @@ typedef enum {
  * unrounded.  Those two products do twice the work.  It is for callers who need every element of large outputs
  * within 2e-2 of an unrounded reference: with EC_BF16 a token's output row scales with its gate values while that
  * error measure is relative to the whole tensor, and the worst element of tens of millions reaches 2-3e-2.
- * Honoured by ec_moe_expert_ffn, ec_moe_forward, ec_moe_forward_grouped, ec_moe_backward(_timed) and
+ * Honoured by ec_moe_expert_ffn, every ec_moe_forward* entry point, ec_moe_backward(_timed) and
  * ec_moe_workspace_bytes (d and d_ff multiples of 64, else EC_ERR_UNSUPPORTED); the routing and data-movement
- * entry points treat it as EC_BF16; the token-choice and capped layers return EC_ERR_UNSUPPORTED. */
+ * entry points, and layers with identity experts, treat it as EC_BF16. */
 typedef enum { EC_F32 = 0, EC_BF16 = 1, EC_BF16_HILO = 2 } ec_dtype;
 typedef enum { EC_ACT_RELU = 0, EC_ACT_GELU = 1 /* exact erf form */, EC_ACT_IDENTITY = 2 } ec_act;
 

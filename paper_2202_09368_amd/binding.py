@@ -232,7 +232,8 @@ def ec_moe_token_choice(S, m: int, cap: int, G, I, load, ws) -> None:
 
 
 def ec_moe_forward_token_choice(X, Wg, W1, W2, c: float, m: int, Xout, act: int, ws, S_out=None, G_out=None,
-                                I_out=None, load_out=None, Xin_out=None, A_out=None, H_out=None, Xe_out=None) -> None:
+                                I_out=None, load_out=None, Xin_out=None, A_out=None, H_out=None, Xe_out=None,
+                                hilo: bool = False) -> None:
     n, d = X.shape
     e = Wg.shape[1]
     d_ff = W1.shape[2] if W1 is not None else 0
@@ -241,7 +242,7 @@ def ec_moe_forward_token_choice(X, Wg, W1, W2, c: float, m: int, Xout, act: int,
     _check("ec_moe_forward_token_choice", lib().ec_moe_forward_token_choice(
         _ptr(X), _ptr(Wg, dt), _ptr(W1, dt), _ptr(W2, dt), c, m, _ptr(Xout, dt), _ptr(S_out, torch.float32),
         _ptr(G_out, torch.float32), _ptr(I_out, torch.int32), _ptr(load_out, torch.int32), _ptr(Xin_out, dt),
-        _ptr(A_out, dt), _ptr(H_out, dt), _ptr(Xe_out, dt), n, d, e, d_ff, act, _dtype_code(X), wp, wb, _stream()))
+        _ptr(A_out, dt), _ptr(H_out, dt), _ptr(Xe_out, dt), n, d, e, d_ff, act, _dtype_code(X, hilo), wp, wb, _stream()))
 
 
 def ec_moe_capped_workspace_bytes(n: int, e: int) -> int:
@@ -256,7 +257,7 @@ def ec_moe_capped_assignment(St, k: int, b: float, lam: float, iters: int, A, ws
 
 
 def ec_moe_forward_capped(X, Wg, W1, W2, c: float, b: float, lam: float, iters: int, Xout, act: int, ws,
-                          S_out=None, G_out=None, I_out=None, A_out=None, Xe_out=None) -> None:
+                          S_out=None, G_out=None, I_out=None, A_out=None, Xe_out=None, hilo: bool = False) -> None:
     n, d = X.shape
     e = Wg.shape[1]
     d_ff = W1.shape[2] if W1 is not None else 0
@@ -265,7 +266,7 @@ def ec_moe_forward_capped(X, Wg, W1, W2, c: float, b: float, lam: float, iters: 
     _check("ec_moe_forward_capped", lib().ec_moe_forward_capped(
         _ptr(X), _ptr(Wg, dt), _ptr(W1, dt), _ptr(W2, dt), c, b, lam, iters, _ptr(Xout, dt),
         _ptr(S_out, torch.float32), _ptr(G_out, torch.float32), _ptr(I_out, torch.int32), _ptr(A_out, torch.float32),
-        _ptr(Xe_out, dt), n, d, e, d_ff, act, _dtype_code(X), wp, wb, _stream()))
+        _ptr(Xe_out, dt), n, d, e, d_ff, act, _dtype_code(X, hilo), wp, wb, _stream()))
 
 
 def ec_moe_backward(dY, X, Wg, W1, W2, S, G, I, Xin, A, H, Xe, dX, dWg, dW1, dW2, act: int, ws, hilo: bool = False) -> None:

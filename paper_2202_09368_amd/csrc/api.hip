@@ -188,6 +188,26 @@ int ec_moe_combine_static(const void* Xe, const float* G, const int32_t* I, void
     return combine_static(Xe, G, I, Xout, n, d, e, k, dtype, (hipStream_t)stream);
 }
 
+// The expert products of Eq. 3 and the sum of Eq. 4 on filled buckets: rows of the buckets come from Xin, or from X
+// through I when Xin == nullptr (the gather fused into the first product).  `hilo`: H leaves the first product as
+// high part + remainder and X_e reaches the sum unrounded (the bf16 X_e is written only for a caller who asks for it).
+static int experts_then_combine(const void* Xin, const void* X, const int32_t* I, const float* G, const void* W1,
+                                const void* W2, void* Xout, void* Xe_out, void* A_out, void* H_out, int64_t n, int64_t d,
+                                int64_t e, int64_t k, int64_t d_ff, int act, int dtype, bool hilo, void* ws,
+                                const WsLayout& L, const CombineIndex& ix, hipStream_t st) {
+    void* H = H_out ? H_out : at(ws, L.h);
+    if (hilo) {
+        float* Xe32 = (float*)at(ws, L.xe32);
+        int rc = launch_ffn(Xin, X, I, n, W1, W2, Xe_out, A_out, H, e, k, d, d_ff, act, dtype, st, at(ws, L.h_lo), Xe32);
+        if (rc != EC_OK) return rc;
+        return launch_combine(Xe32, G, I, Xout, n, d, e, k, dtype, ix, st, nullptr, false, nullptr, true);
+    }
+    void* Xe = Xe_out ? Xe_out : at(ws, L.xe);
+    int rc = launch_ffn(Xin, X, I, n, W1, W2, Xe, A_out, H, e, k, d, d_ff, act, dtype, st);
+    if (rc != EC_OK) return rc;
+    return launch_combine(Xe, G, I, Xout, n, d, e, k, dtype, ix, st);
+}
+
 // The layer with TopK taken inside each of `groups` equal runs of tokens (groups = 1: Eq. 2 as printed).
 static int forward_impl(const void* X, const void* Wg, const void* W1, const void* W2, double c, int64_t groups,
                         void* Xout, float* S_out, float* G_out, int32_t* I_out, void* Xin_out, void* A_out,
@@ -246,20 +266,8 @@ static int forward_impl(const void* X, const void* Wg, const void* W1, const voi
         rc = launch_dispatch(X, I, Xin, n, d, e, k, dtype, st);
         if (rc != EC_OK) return rc;
     }
-    void* H = H_out ? H_out : at(ws, L.h);
-    if (hilo) {
-        // H leaves the first product as high part + remainder, X_e reaches the sum of Eq. 4 unrounded (the bf16 X_e
-        // is written only for a caller who asks for it)
-        float* Xe32 = (float*)at(ws, L.xe32);
-        rc = launch_ffn(fused_gather ? nullptr : Xin, X, I, n, W1, W2, Xe_out, A_out, H, e, k, d, d_ff, act, dtype, st,
-                        at(ws, L.h_lo), Xe32);
-        if (rc != EC_OK) return rc;
-        return launch_combine(Xe32, G, I, Xout, n, d, e, k, dtype, ix, st, nullptr, false, nullptr, true);
-    }
-    void* Xe = Xe_out ? Xe_out : at(ws, L.xe);
-    rc = launch_ffn(fused_gather ? nullptr : Xin, X, I, n, W1, W2, Xe, A_out, H, e, k, d, d_ff, act, dtype, st);
-    if (rc != EC_OK) return rc;
-    return launch_combine(Xe, G, I, Xout, n, d, e, k, dtype, ix, st);
+    return experts_then_combine(fused_gather ? nullptr : Xin, X, I, G, W1, W2, Xout, Xe_out, A_out, H_out, n, d, e, k,
+                                d_ff, act, dtype, hilo, ws, L, ix, st);
 }
 
 int ec_moe_forward(const void* X, const void* Wg, const void* W1, const void* W2, double c, void* Xout,
@@ -294,7 +302,6 @@ int ec_moe_forward_token_choice(const void* X, const void* Wg, const void* W1, c
                                 int64_t d_ff, int act, int dtype, void* ws, size_t ws_bytes, void* stream) {
     int64_t k = 0;  // rows of an expert's buffer
     if (ec_moe_capacity(n, e, c, &k) != EC_OK || m < 1 || m > e || m > 8) return EC_ERR_INVALID_ARG;
-    if (dtype == EC_BF16_HILO) return EC_ERR_UNSUPPORTED;
     const bool identity = (W1 == nullptr && W2 == nullptr);
     if (!X || !Wg || !Xout || !sizes_ok(n, d, e, k) || !dtype_ok(dtype) || !act_ok(act) || !width_ok(d, dtype) ||
         !all_aligned(X, Wg, W1, W2, Xout, S_out, G_out, I_out, load_out, Xin_out, A_out, H_out, Xe_out))
@@ -308,6 +315,10 @@ int ec_moe_forward_token_choice(const void* X, const void* Wg, const void* W1, c
     }
     const WsLayout L = ws_layout(n, d, e, k, d_ff, dtype, 0);
     if (!ws_ok(ws, ws_bytes, L.total)) return EC_ERR_WORKSPACE;
+    bool hilo = false;
+    dtype = storage_dtype(dtype, &hilo);
+    if (identity) hilo = false;
+    if (hilo && !ffn_can_hilo(dtype, k, d, d_ff)) return EC_ERR_UNSUPPORTED;
     hipStream_t st = (hipStream_t)stream;
 
     float* S = S_out ? S_out : (float*)at(ws, L.st);  // [n, e]: the same size as the S^T region
@@ -327,15 +338,9 @@ int ec_moe_forward_token_choice(const void* X, const void* Wg, const void* W1, c
         rc = launch_dispatch(X, I, Xin, n, d, e, k, dtype, st);
         if (rc != EC_OK) return rc;
     }
-    const void* Xe = Xin;
-    if (!identity) {
-        void* Xe_w = Xe_out ? Xe_out : at(ws, L.xe);
-        rc = launch_ffn(fused_gather ? nullptr : Xin, X, I, n, W1, W2, Xe_w, A_out, H_out ? H_out : at(ws, L.h), e, k, d,
-                        d_ff, act, dtype, st);
-        if (rc != EC_OK) return rc;
-        Xe = Xe_w;
-    }
-    return launch_combine(Xe, G, I, Xout, n, d, e, k, dtype, ix, st);
+    if (identity) return launch_combine(Xin, G, I, Xout, n, d, e, k, dtype, ix, st);
+    return experts_then_combine(fused_gather ? nullptr : Xin, X, I, G, W1, W2, Xout, Xe_out, A_out, H_out, n, d, e, k,
+                                d_ff, act, dtype, hilo, ws, L, ix, st);
 }
 
 size_t ec_moe_capped_workspace_bytes(int64_t n, int64_t e) {
@@ -361,7 +366,6 @@ int ec_moe_forward_capped(const void* X, const void* Wg, const void* W1, const v
                           int dtype, void* ws, size_t ws_bytes, void* stream) {
     int64_t k = 0;
     if (ec_moe_capacity(n, e, c, &k) != EC_OK || !capped_args_ok(b, lambda, iters)) return EC_ERR_INVALID_ARG;
-    if (dtype == EC_BF16_HILO) return EC_ERR_UNSUPPORTED;
     const bool identity = (W1 == nullptr && W2 == nullptr);
     if (!X || !Wg || !Xout || !sizes_ok(n, d, e, k) || !dtype_ok(dtype) || !act_ok(act) || !width_ok(d, dtype) ||
         !all_aligned(X, Wg, W1, W2, Xout, S_out, G_out, I_out, A_out, Xe_out))
@@ -377,6 +381,10 @@ int ec_moe_forward_capped(const void* X, const void* Wg, const void* W1, const v
     // after the layer's own regions: the solver's state, then A when the caller does not want it
     const size_t a_bytes = align_up((size_t)e * n * 4, 256);
     if (!ws_ok(ws, ws_bytes, L.total + capped_ws_bytes(n, e) + a_bytes)) return EC_ERR_WORKSPACE;
+    bool hilo = false;
+    dtype = storage_dtype(dtype, &hilo);
+    if (identity) hilo = false;
+    if (hilo && !ffn_can_hilo(dtype, k, d, d_ff)) return EC_ERR_UNSUPPORTED;
     hipStream_t st = (hipStream_t)stream;
 
     float* St = (float*)at(ws, L.st);
@@ -402,15 +410,9 @@ int ec_moe_forward_capped(const void* X, const void* Wg, const void* W1, const v
         rc = launch_dispatch(X, I, Xin, n, d, e, k, dtype, st);
         if (rc != EC_OK) return rc;
     }
-    const void* Xe = Xin;
-    if (!identity) {
-        void* Xe_w = Xe_out ? Xe_out : at(ws, L.xe);
-        rc = launch_ffn(fused_gather ? nullptr : Xin, X, I, n, W1, W2, Xe_w, nullptr, at(ws, L.h), e, k, d, d_ff, act,
-                        dtype, st);
-        if (rc != EC_OK) return rc;
-        Xe = Xe_w;
-    }
-    return launch_combine(Xe, G, I, Xout, n, d, e, k, dtype, ix, st);
+    if (identity) return launch_combine(Xin, G, I, Xout, n, d, e, k, dtype, ix, st);
+    return experts_then_combine(fused_gather ? nullptr : Xin, X, I, G, W1, W2, Xout, Xe_out, nullptr, nullptr, n, d, e, k,
+                                d_ff, act, dtype, hilo, ws, L, ix, st);
 }
 
 int ec_moe_backward(const void* dY, const void* X, const void* Wg, const void* W1, const void* W2, const float* S,

@@ -102,13 +102,15 @@ def test_invalid_arguments_are_rejected_on_the_host(m):
     assert fwd(P, None, 2.0, 1, P, 1 << 30) == INV
     assert fwd(P, P, 2.0, 1, None, 0) == WS
     assert fwd(P, P, 2.0, 1, P, 64) == WS
-    # two-part intermediates: widths outside the matrix-core path, and the two routing variants, are refused
+    # two-part intermediates: widths outside the matrix-core path are refused
     UNS = -4
     assert lib.ec_moe_forward(P, P, P, P, 2.0, P, None, None, None, None, None, None, None, 64, 16, 4, 32, 1,
                               m.EC_BF16_HILO, P, 1 << 30, None) == UNS
     assert lib.ec_moe_expert_ffn(P, P, P, P, None, None, 2, 4, 16, 32, 1, m.EC_BF16_HILO, P, 1 << 20, None) == UNS
-    assert lib.ec_moe_forward_token_choice(P, P, P, P, 2.0, 2, P, None, None, None, None, None, None, None, None, 64, 64,
-                                           16, 128, 1, m.EC_BF16_HILO, P, 1 << 30, None) == UNS
+    assert lib.ec_moe_forward_token_choice(P, P, P, P, 2.0, 2, P, None, None, None, None, None, None, None, None, 64, 16,
+                                           16, 32, 1, m.EC_BF16_HILO, P, 1 << 30, None) == UNS
+    assert lib.ec_moe_forward_capped(P, P, P, P, 2.0, 2.0, 1e-3, 10, P, None, None, None, None, None, 64, 16, 4, 32, 1,
+                                     m.EC_BF16_HILO, P, 1 << 30, None) == UNS
     assert lib.ec_moe_backward(*([P] * 16 + [64, 16, 4, 32, 32, 1, m.EC_BF16_HILO, P, 1 << 40, None])) == UNS
     # grouped top-k: the groups must cut the tokens into equal runs; k_g within a run
     assert lib.ec_moe_topk_tokens_grouped(P, 10, 2, 3, 1, P, P, None, 0, None) == INV

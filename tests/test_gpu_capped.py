@@ -70,8 +70,11 @@ def test_capped_assignment(m, ref, n, e, k, b, lam, iters, scale):
     ("cfg3", dict(n=2048, d=128, e=64, d_ff=256), 3.0, 60),
     ("cfg5", dict(n=4096, d=128, e=32), 1.0, 100),                       # identity experts
     ("cfg2", dict(), 2.0, 100),                                          # full size, as `bench.py --capped 2` runs it
+    ("cfg2", dict(n=2048, d=256, e=16, d_ff=512, hilo=True), 2.0, 100),  # two-part H, unrounded X_e into the sum
 ])
 def test_capped_forward(m, ref, base, kw, b, iters):
+    kw = dict(kw)
+    hilo = kw.pop("hilo", False)
     w = sized(wl.WORKLOADS[base], **kw)
     inp = wl.make_inputs(w)
     n, d, e = w.n, w.d, w.e
@@ -79,8 +82,8 @@ def test_capped_forward(m, ref, base, kw, b, iters):
     lam = 1e-3
     _p(f"[capped forward] {base} n={n} d={d} e={e} k={k} b={b} iters={iters}")
     dt = torch_dtype(w)
-    nbytes = m.ec_moe_workspace_bytes(n, d, e, k, w.d_ff, w.dtype) + m.ec_moe_capped_workspace_bytes(n, e) \
-        + (4 * e * n + 255) // 256 * 256
+    nbytes = m.ec_moe_workspace_bytes(n, d, e, k, w.d_ff, m.EC_BF16_HILO if hilo else w.dtype) \
+        + m.ec_moe_capped_workspace_bytes(n, e) + (4 * e * n + 255) // 256 * 256
     ws = torch.empty(nbytes, dtype=torch.uint8, device="cuda")
     t = {key: to_dev(inp[key]) for key in ("X", "Wg", "W1", "W2") if key in inp}
     Xout = torch.empty((n, d), dtype=dt, device="cuda")
@@ -90,7 +93,7 @@ def test_capped_forward(m, ref, base, kw, b, iters):
     I = torch.empty((e, k), dtype=torch.int32, device="cuda")
     Xe = torch.empty((e, k, d), dtype=dt, device="cuda") if w.d_ff else None
     m.ec_moe_forward_capped(t["X"], t["Wg"], t.get("W1"), t.get("W2"), w.c, b, lam, iters, Xout, w.act, ws,
-                            S_out=S, G_out=G, I_out=I, A_out=A, Xe_out=Xe)
+                            S_out=S, G_out=G, I_out=I, A_out=A, Xe_out=Xe, hilo=hilo)
     torch.cuda.synchronize()
     S_h, A_h, G_h, I_h = to_host(S), to_host(A), to_host(G), to_host(I)
     S_ref = ref.gate(inp["X"], inp["Wg"])
@@ -113,7 +116,7 @@ def test_capped_forward(m, ref, base, kw, b, iters):
         Xe_ref = ref.widen(X_in)
     err = max_rel_err(to_host(Xout), ref.combine(Xe_ref, G_h, I_h, n))
     _p(f"[capped forward] X_out max rel err {err:.3e}")
-    assert err <= out_tol(w)
+    assert err <= (5e-3 if hilo else out_tol(w))    # two-part intermediates: what is left is the rounding of X_out
 
 
 @pytest.mark.parametrize("base,kw,b,tol", [
