@@ -369,6 +369,12 @@ def _topk_case(m, ref, St_h, k):
     (12, 2, 5, "rand"), (4096, 3, 100, "rand"), (4100, 3, 100, "rand"),   # around the register-tile edges
     (65536, 2, 256, "rand"), (65536, 2, 40000, "levels"), (65536, 2, 300, "const"),
     (65540, 2, 256, "rand"), (32768, 2, 512, "onehot"), (16384, 3, 16384, "levels"),
+    # rows of more than 32768 scores with k <= 512 take a threshold from the per-thread maxima first: rows where
+    # that threshold works (rand, softmax), where it keeps too many candidates and the general path takes over
+    # (sorted rows, ties at the threshold), partial last register tiles, k = 1 and k = 512
+    (65536, 3, 512, "rand"), (65536, 2, 1, "rand"), (40000, 3, 100, "rand"), (32772, 2, 512, "rand"),
+    (65536, 2, 256, "sorted_desc"), (65536, 2, 256, "sorted_asc"), (50000, 2, 384, "levels"),
+    (65536, 2, 200, "onehot"), (65536, 2, 256, "spikes"), (65536, 2, 512, "tiny_range"), (65536, 4, 256, "softmax"),
 ])
 def test_topk_cases(m, ref, n, e, k, kind):
     _p(f"[topk] n={n} e={e} k={k} {kind}")
@@ -381,6 +387,18 @@ def test_topk_cases(m, ref, n, e, k, kind):
         St = (np.floor(r.random((e, n)) * 5) / 5).astype(np.float32)
     elif kind == "onehot":
         St = (r.random((e, n)) < 0.3).astype(np.float32)
+    elif kind == "sorted_desc":
+        St = -np.sort(-r.random((e, n), dtype=np.float32), axis=1)
+    elif kind == "sorted_asc":
+        St = np.sort(r.random((e, n), dtype=np.float32), axis=1)
+    elif kind == "spikes":        # exactly k - 3 large scores, the rest zero: the cut-off falls among tied zeros
+        St = np.zeros((e, n), np.float32)
+        for i in range(e):
+            St[i, r.choice(n, k - 3, replace=False)] = 0.5 + 0.5 * r.random(k - 3, dtype=np.float32)
+    elif kind == "softmax":       # scores of a gate: one softmax per token over 64 experts, the first e of them kept
+        z = r.standard_normal((64, n)) * 3.0
+        p = np.exp(z - z.max(axis=0, keepdims=True))
+        St = np.ascontiguousarray((p / p.sum(axis=0, keepdims=True)).astype(np.float32)[:e])
     else:
         base = np.float32(0.003)
         St = (base.view(np.uint32) + r.integers(0, 4, (e, n)).astype(np.uint32)).view(np.float32)
