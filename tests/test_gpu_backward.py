@@ -209,13 +209,14 @@ def _cfg4_full(m, ref, hilo):
                      + "; ".join(over_the_bar))
 
 
-def test_backward_timed_is_the_same_pass(m):
+@pytest.mark.parametrize("hilo", [False, True])
+def test_backward_timed_is_the_same_pass(m, hilo):
     """ec_moe_backward_timed: the gradients of ec_moe_backward bit for bit, plus one duration per stage."""
     w = sized(wl.WORKLOADS["cfg2"], backward=True, n=2048, d=256, e=8, d_ff=512)
     inp = wl.make_inputs(w)
     n, d, e, k, f = w.n, w.d, w.e, w.k, w.d_ff
     t = {key: to_dev(inp[key]) for key in ("X", "Wg", "W1", "W2", "dY")}
-    ws = m.alloc_workspace(n, d, e, k, f, w.dtype, with_backward=True)
+    ws = m.alloc_workspace(n, d, e, k, f, m.EC_BF16_HILO if hilo else w.dtype, with_backward=True)
     dev = dict(device="cuda")
     bf, f32 = torch.bfloat16, torch.float32
     S = torch.empty((n, e), dtype=f32, **dev)
@@ -225,7 +226,7 @@ def test_backward_timed_is_the_same_pass(m):
     A, H = (torch.empty((e, k, f), dtype=bf, **dev) for _ in range(2))
     Xout = torch.empty((n, d), dtype=bf, **dev)
     m.ec_moe_forward(t["X"], t["Wg"], t["W1"], t["W2"], w.c, Xout, w.act, ws, S_out=S, G_out=G, I_out=I,
-                     Xin_out=Xin, A_out=A, H_out=H, Xe_out=Xe)
+                     Xin_out=Xin, A_out=A, H_out=H, Xe_out=Xe, hilo=hilo)
     outs = []
     for timed in (False, True):
         dX = torch.full((n, d), float("nan"), dtype=bf, **dev)
@@ -234,12 +235,12 @@ def test_backward_timed_is_the_same_pass(m):
         dW2 = torch.full((e, f, d), float("nan"), dtype=f32, **dev)
         args = (t["dY"], t["X"], t["Wg"], t["W1"], t["W2"], S, G, I, Xin, A, H, Xe, dX, dWg, dW1, dW2, w.act, ws)
         if timed:
-            ms = m.ec_moe_backward_timed(*args)
+            ms = m.ec_moe_backward_timed(*args, hilo=hilo)
             assert list(ms) == ["bwd_rows", "bwd_dW2", "bwd_dA", "bwd_dW1", "bwd_dX_in", "bwd_index", "bwd_dZ",
                                 "bwd_gate_products", "bwd_scatter"]
             assert all(0.0 < v < 1e3 for v in ms.values()), ms
         else:
-            m.ec_moe_backward(*args)
+            m.ec_moe_backward(*args, hilo=hilo)
         torch.cuda.synchronize()
         outs.append([to_host(x) for x in (dX, dWg, dW1, dW2)])
     for a, b in zip(*outs):

@@ -78,8 +78,11 @@ def test_grouped_topk_rejects_bad_groups(m):
     ("cfg2", dict(), 8),                                               # full size, as `bench.py --groups 8` runs it
     ("cfg2", dict(n=4096, d=256, e=16, d_ff=512), 32),                 # runs of 128 tokens: the small-segment kernel
     ("cfg3", dict(n=4096, d=128, e=64, d_ff=256), 64),
+    ("cfg2", dict(n=4096, d=256, e=16, d_ff=512, hilo=True), 8),       # two-part H, unrounded X_e into the sum
 ])
 def test_grouped_forward(m, ref, base, kw, groups):
+    kw = dict(kw)
+    hilo = kw.pop("hilo", False)
     w = sized(wl.WORKLOADS[base], **kw)
     inp = wl.make_inputs(w)
     n, d, e = w.n, w.d, w.e
@@ -87,7 +90,7 @@ def test_grouped_forward(m, ref, base, kw, groups):
     k = groups * k_g
     _p(f"[grouped forward] {base} n={n} d={d} e={e} groups={groups} k_g={k_g}")
     dt = torch_dtype(w)
-    ws = m.alloc_workspace(n, d, e, k, w.d_ff, w.dtype)
+    ws = m.alloc_workspace(n, d, e, k, w.d_ff, m.EC_BF16_HILO if hilo else w.dtype)
     t = {key: to_dev(inp[key]) for key in ("X", "Wg", "W1", "W2") if key in inp}
     Xout = torch.empty((n, d), dtype=dt, device="cuda")
     S = torch.empty((n, e), dtype=torch.float32, device="cuda")
@@ -95,7 +98,7 @@ def test_grouped_forward(m, ref, base, kw, groups):
     I = torch.empty((e, k), dtype=torch.int32, device="cuda")
     Xe = torch.empty((e, k, d), dtype=dt, device="cuda") if w.d_ff else None
     m.ec_moe_forward_grouped(t["X"], t["Wg"], t.get("W1"), t.get("W2"), w.c, groups, Xout, w.act, ws,
-                             S_out=S, G_out=G, I_out=I, Xe_out=Xe)
+                             S_out=S, G_out=G, I_out=I, Xe_out=Xe, hilo=hilo)
     torch.cuda.synchronize()
     S_h, G_h, I_h = to_host(S), to_host(G), to_host(I)
     S_ref = ref.gate(inp["X"], inp["Wg"])
@@ -112,9 +115,9 @@ def test_grouped_forward(m, ref, base, kw, groups):
     Xout_ref = ref.combine(Xe_ref, G_h, I_h, n)
     err = max_rel_err(to_host(Xout), Xout_ref)
     _p(f"[grouped forward] X_out max rel err {err:.3e}")
-    assert err <= out_tol(w)
+    assert err <= (5e-3 if hilo else out_tol(w))    # two-part intermediates: what is left is the rounding of X_out
     # the plain entry point is the one-group case
-    if groups > 1:
+    if groups > 1 and not hilo:
         Xout1 = torch.empty_like(Xout)
         Xout2 = torch.empty_like(Xout)
         ws1 = m.alloc_workspace(n, d, e, ref.capacity(n, w.c, e), w.d_ff, w.dtype)
