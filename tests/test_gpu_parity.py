@@ -171,8 +171,9 @@ def _stagewise(m, ref, w, inp, check_ffn=True, ffn_experts=None):
                    f"roundings is at {e_mir:.3e}; kernels vs that: {e_between:.3e}")
                 assert e_between <= out_tol(w) and err <= e_mir + 5e-3
                 notes.append(f"{label}: {err:.3e} (rounding recipe alone: {e_mir:.3e})")
-            pytest.xfail(f"{w.name} X_out over the 2e-2 bar against the unrounded float64 oracle on its worst element of "
-                         f"{n * d}: " + "; ".join(notes))
+            pytest.xfail(f"{w.name} X_out in EC_BF16 (single bf16 intermediates; EC_BF16_HILO meets the bar, see the _hilo "
+                         f"test) over the 2e-2 bar against the unrounded float64 oracle on its worst element of {n * d}: "
+                         + "; ".join(notes))
         assert not missed, missed
     elif w.d_ff > 0 and check_ffn:
         # whole layer on the tokens routed only to the sampled experts
