@@ -38,6 +38,43 @@ def _scores(rng, kind, n, e):
     return (p / p.sum(1, keepdims=True)).astype(np.float32)
 
 
+def test_random_long_rows(m, ref):
+    """Rows of more than 32768 scores with small buckets: the selection first tries a threshold taken from the
+    per-thread maxima and falls back to the radix passes when that keeps too many candidates.  Random row lengths
+    (partial register tiles), bucket sizes on both sides of 512, and score layouts that hit both outcomes."""
+    rng = np.random.default_rng(77)
+    for it in range(24):
+        seg = int(rng.integers(32768 // 4 + 1, 65536 // 4 + 1)) * 4
+        groups = 2 if it % 6 == 5 else 1
+        n, e = seg * groups, int(rng.integers(1, 4))
+        k = int(rng.choice([1, 2, 37, 128, 256, 300, 511, 512, 513, 700]))
+        kind = it % 6
+        if kind in (0, 5):
+            S = rng.random((n, e), dtype=np.float32)
+        elif kind == 1:                               # gate-like: softmax over 64 experts, the first e kept
+            z = rng.standard_normal((n, 64)) * 4
+            p = np.exp(z - z.max(1, keepdims=True))
+            S = np.ascontiguousarray((p / p.sum(1, keepdims=True)).astype(np.float32)[:, :e])
+        elif kind == 2:                               # blocks of 4096 sorted tokens: the large scores sit in few threads
+            S = rng.random((n, e), dtype=np.float32)
+            for b in range(0, n, 4096):
+                S[b:b + 4096] = -np.sort(-S[b:b + 4096], axis=0)
+        elif kind == 3:                               # 16 distinct values: ties at every threshold
+            S = (np.floor(rng.random((n, e)) * 16) / 16).astype(np.float32)
+        else:                                         # a few hundred large scores over a floor of equal ones
+            S = np.full((n, e), 0.001, np.float32)
+            for i in range(e):
+                idx = rng.choice(n, int(rng.integers(1, 2 * k + 2)), replace=False)
+                S[idx, i] = 0.5 + 0.5 * rng.random(idx.size, dtype=np.float32)
+        print(f"[long rows {it}] layout {kind} n={n} e={e} groups={groups} k_g={k}", flush=True)
+        G = torch.empty((e, groups * k), dtype=torch.float32, device="cuda")
+        I = torch.empty((e, groups * k), dtype=torch.int32, device="cuda")
+        m.ec_moe_topk_tokens_grouped(to_dev(np.ascontiguousarray(S.T)), groups, k, G, I)
+        torch.cuda.synchronize()
+        G_o, I_o = ref.topk_tokens_grouped(S, k, groups)
+        assert (to_host(I) == I_o).all() and (to_host(G).view(np.uint32) == G_o.view(np.uint32)).all()
+
+
 def test_random_routing_problems(m, ref):
     rng = np.random.default_rng(2024)
     done = 0
